@@ -1,0 +1,173 @@
+/*
+ * moehot.h -- C ABI of libmoehot: one GPU's share of an expert-parallel MoE layer on MI355X.
+ *
+ * The calls follow the workflow of an expert-parallel MoE layer as the Pro-Prophet paper
+ * (arXiv 2411.10003) states it: the gate routes every input to its top-k experts (Section 2.1),
+ * the number of inputs per expert is the "input distribution" the planner consumes (Section 3),
+ * inputs are exchanged by an all-to-all according to an expert placement in which a device that
+ * holds an expert's parameters computes its local inputs itself (Section 4.1), every device runs
+ * the expert computation over the inputs it hosts (Section 4.2, Eq. 2-3), and a second all-to-all
+ * returns the results to the inputs' original positions (Section 2.1, Fig. 2).  On one GPU the
+ * all-to-all destinations are only a buffer layout.
+ *
+ * Conventions
+ *   - Every pointer is DEVICE memory owned by the caller unless marked "host".  The library
+ *     allocates no device memory; scratch comes from the caller's workspace (moe_workspace_bytes).
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it; they never
+ *     synchronise and never read device data on the host (moe_read_status excepted).
+ *   - Arguments are checked on the host before anything is launched.  Return value: MOE_OK or a
+ *     negative moe_status_t; on an error nothing has been enqueued.
+ *   - Outputs are overwritten, never accumulated into.  Same inputs give the same bits.
+ *   - Row-major everywhere.  "elt" is the activation type of the handle: float (MOE_F32) or
+ *     bfloat16 (MOE_BF16, upper half of an IEEE float, round-to-nearest-even).  Gate parameters,
+ *     logits, gate weights and weight gradients are always float; indices are int32_t.
+ *   - Notation: T tokens, d model width, h hidden width, E experts, k experts per token,
+ *     P destinations, A = T*k assignments with id a = t*k + j, G hosted weight groups.
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef MOEHOT_H
+#define MOEHOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_NULL = -1,          /* a required pointer is NULL */
+    MOE_ERR_SHAPE = -2,         /* unsupported or inconsistent sizes */
+    MOE_ERR_PLAN = -3,          /* placement out of range (reported by moe_read_status) */
+    MOE_ERR_WORKSPACE = -4,     /* workspace missing or misaligned */
+    MOE_ERR_DTYPE = -5,
+    MOE_ERR_UNIMPLEMENTED = -6,
+    MOE_ERR_HIP = -7            /* a HIP call failed; see moe_last_hip_error() */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+typedef enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 } moe_act_t;
+
+/* Problem description, fixed per handle.
+ *   self   : destination id of this GPU in [0, P).
+ *   G      : capacity of the hosted weight arrays (owned + replicated experts), 1 <= G <= E.
+ *   renorm : 1 = the k gate weights of a token are renormalised to sum to one.
+ * Limits: 1 <= k <= 8, k <= E <= 1024, 1 <= P <= E; MOE_BF16 needs d % 64 == 0 and h % 64 == 0;
+ * T*k < 2^31 / max(d, h) is not required (row offsets are 64-bit) but T*k < 2^31 is. */
+typedef struct {
+    int T, d, h, E, k, P, self, G;
+    moe_dtype_t dtype;
+    moe_act_t act;
+    int renorm;
+} moe_shape_t;
+
+/* Send layout produced by moe_dispatch (all device pointers, int32_t):
+ *   slot_of_expert[E]  slot index of each expert; slots are the experts ordered by
+ *                      (expert_dest[e], e), so a destination's slots and rows are contiguous
+ *   slot_offsets[E+1]  first row of each slot; slot_offsets[E] = A
+ *   dest_offsets[P+1]  first row of each destination (the all-to-all send displacements)
+ *   dest_slots[P+1]    first slot of each destination
+ *   pos[A]             row of assignment a (stable: ascending a inside a slot)
+ *   perm[A]            assignment held by each row; perm[pos[a]] = a
+ * The hosted groups are the slots dest_slots[self] .. dest_slots[self+1]-1, in that order
+ * (ascending expert id); group g uses W*[g].  At most G groups are computed. */
+typedef struct {
+    int32_t* slot_of_expert;
+    int32_t* slot_offsets;
+    int32_t* dest_offsets;
+    int32_t* dest_slots;
+    int32_t* pos;
+    int32_t* perm;
+} moe_layout_t;
+
+typedef struct moe_ctx* moe_handle_t;
+
+/* Create / destroy a handle (host objects only).  *out is written on success. */
+int moe_create(moe_handle_t* out, const moe_shape_t* shape);
+int moe_destroy(moe_handle_t h);
+
+/* Bytes of workspace every call below may use (256-byte aligned device memory). */
+int moe_workspace_bytes(moe_handle_t h, size_t* bytes);
+
+const char* moe_status_string(int status);
+/* Last hipError_t seen by this thread's calls, as an int (0 = hipSuccess). */
+int moe_last_hip_error(void);
+
+/* Synchronises `stream` and copies the device-side status word of the workspace to *status (host):
+ * MOE_OK, or MOE_ERR_PLAN if the last moe_dispatch saw expert_dest outside [0,P) or more than G
+ * hosted experts.  The only call that blocks. */
+int moe_read_status(moe_handle_t h, const void* ws, void* stream, int* status);
+
+/* Gate and routing (Section 2.1: the gate relates an input to all experts and routes it to the
+ * top-k).  logits[t,e] = bg[e] + sum_c X[t,c] * Wg[c,e] in fp32 with a fixed summation order
+ * (64 column-strided partial sums built with fused multiply-adds, folded by halving offsets, bias
+ * last) so that routing is reproducible bit for bit.  idx[t,0..k) = the k largest logits, best
+ * first, ties to the lowest index, NaN ranked as -inf.  p = softmax(logits[t,:]);
+ * w[t,j] = p[idx[t,j]], divided by their sum over j when renorm = 1.
+ *   in : X[T,d] elt, Wg[d,E] float, bg[E] float
+ *   out: logits[T,E] float, idx[T,k] int32, w[T,k] float */
+int moe_gate_topk(moe_handle_t h, const void* X, const float* Wg, const float* bg,
+                  float* logits, int32_t* idx, float* w, void* stream);
+
+/* Input distribution (Section 3: the number of inputs each expert processes; what the planner's
+ * search consumes).  in: idx[A]; out: counts[E].  Uses the workspace. */
+int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void* ws, void* stream);
+
+/* Placement-aware send buffer (Section 4.1: inputs of an expert whose parameters are on this
+ * device are computed locally, the others go to the expert's owner; Fig. 2: first all-to-all).
+ *   in : expert_dest[E] int32 in [0,P): destination that computes this GPU's inputs of expert e
+ *        (== self for owned and replicated experts); X[T,d] elt; idx[A]; counts[E] as returned by
+ *        moe_expert_counts for the same idx
+ *   out: every array of *layout (host struct of device pointers); Xp[A,d] elt with
+ *        Xp[r,:] = X[perm[r] / k, :] (bit copies) */
+int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                 const int32_t* counts, const moe_layout_t* layout, void* Xp, void* ws, void* stream);
+
+/* Forward expert computation over the hosted groups (Section 4.2, Eq. 2), ragged and possibly
+ * empty, without padding:  GELU: Yp = gelu(Xp W1) W2;  SwiGLU: Yp = (silu(Xp W1) * (Xp W3)) W2,
+ * gelu(z) = z/2 (1 + erf(z/sqrt 2)), silu(z) = z / (1 + exp(-z)), fp32 accumulation.
+ *   in : Xp[A,d] elt; layout (slot_offsets, dest_slots are read); W1[G,d,h], W2[G,h,d] elt,
+ *        W3[G,d,h] elt for SwiGLU (NULL otherwise)
+ *   out: rows of the hosted groups only: Yp[A,d] elt, Z[A,h] elt (= Xp W1, kept for backward),
+ *        U[A,h] elt (= Xp W3, SwiGLU only, else NULL).  Other rows are not touched. */
+int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* layout,
+                       const void* W1, const void* W2, const void* W3,
+                       void* Yp, void* Z, void* U, void* ws, void* stream);
+
+/* Weighted return (Fig. 2: second all-to-all, then the sum at the input's original position):
+ * out[t,:] = sum_j w[t,j] * Yp[pos[t*k+j],:], fp32 accumulation in ascending j, rounded once.
+ *   in : Yp[A,d] elt (rows of other destinations are what the return all-to-all delivered),
+ *        pos[A], w[T,k] float;  out: out[T,d] elt */
+int moe_combine(moe_handle_t h, const void* Yp, const int32_t* pos, const float* w, void* out, void* stream);
+
+/* Gradient of moe_combine: dYp[pos[a],:] = w[a] * dOut[t,:];  dw[t,j] = <dOut[t,:], Yp[pos[a],:]>.
+ *   in : dOut[T,d] elt, Yp[A,d] elt, pos[A], w[T,k];  out: dYp[A,d] elt, dw[T,k] float */
+int moe_combine_bwd(moe_handle_t h, const void* dOut, const void* Yp, const int32_t* pos, const float* w,
+                    void* dYp, float* dw, void* stream);
+
+/* Backward expert computation over the hosted groups (Section 4.2, Eq. 3).  With A = act(Z)(*U)
+ * and dA = dYp W2^T:   GELU: dZ = dA * gelu'(Z);   SwiGLU: dU = dA * silu(Z), dZ = dA * U * silu'(Z);
+ * dXp = dZ W1^T (+ dU W3^T);  dW1 = Xp^T dZ, dW3 = Xp^T dU, dW2 = A^T dYp, each over the group's rows.
+ *   in : dYp[A,d], Xp[A,d], Z[A,h], U[A,h] (SwiGLU) elt; layout; W1, W2, W3 as in the forward call
+ *   out: dXp[A,d] elt, rows of hosted groups only; dW1[G,d,h], dW2[G,h,d], dW3[G,d,h] float,
+ *        written for all G groups (zeros for an empty or unused group) */
+int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                       const moe_layout_t* layout, const void* W1, const void* W2, const void* W3,
+                       void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream);
+
+/* Gradient of the send (the backward all-to-all of the dispatch): dX[t,:] = sum_j dXp[pos[t*k+j],:],
+ * the expert-path gradient of the layer input.  in: dXp[A,d] elt, pos[A];  out: dX[T,d] elt */
+int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* dX, void* stream);
+
+/* Gradient of the gate weights with respect to the logits, selection held fixed.
+ *   renorm = 0: dlogits[t,e] = sum_j dw[t,j] p[s_j] ((e == s_j) - p[e])
+ *   renorm = 1: dlogits[t,s_j] = w_j (dw_j - sum_i w_i dw_i), zero elsewhere
+ *   in : dw[T,k] float, logits[T,E] float, idx[T,k];  out: dlogits[T,E] float */
+int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int32_t* idx,
+                 float* dlogits, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEHOT_H */

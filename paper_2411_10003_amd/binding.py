@@ -1,0 +1,259 @@
+"""Thin ctypes binding of libmoehot.so: the same entry points as include/moehot.h, taking torch
+tensors.  Argument marshalling only -- every step of the layer runs in the HIP kernels of the
+library.  PyTorch is used for device memory and streams.  There is no CPU or eager fallback: if
+the library has not been built, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoehot.so")
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_ACT_GELU, MOE_ACT_SWIGLU = 0, 1
+DTYPES = {"f32": MOE_F32, "bf16": MOE_BF16}
+ACTS = {"gelu": MOE_ACT_GELU, "swiglu": MOE_ACT_SWIGLU}
+TORCH_DTYPE = {MOE_F32: torch.float32, MOE_BF16: torch.bfloat16}
+
+EXPORTS = [
+    "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
+    "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
+    "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
+]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({detail})")
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("T", "d", "h", "E", "k", "P", "self", "G", "dtype", "act", "renorm")]
+
+
+class _Layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("slot_of_expert", "slot_offsets", "dest_offsets", "dest_slots", "pos", "perm")]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the HIP library.  Raises if it is missing: nothing else can compute the layer."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2411_10003_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        lib.moe_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_Shape)]
+        lib.moe_destroy.argtypes = [vp]
+        lib.moe_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.moe_status_string.argtypes = [ip]
+        lib.moe_status_string.restype = ctypes.c_char_p
+        lib.moe_read_status.argtypes = [vp, vp, vp, ctypes.POINTER(ip)]
+        lib.moe_gate_topk.argtypes = [vp] * 8
+        lib.moe_expert_counts.argtypes = [vp] * 5
+        lib.moe_dispatch.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(_Layout), vp, vp, vp]
+        lib.moe_expert_ffn_fwd.argtypes = [vp, vp, ctypes.POINTER(_Layout)] + [vp] * 8
+        lib.moe_combine.argtypes = [vp] * 6
+        lib.moe_combine_bwd.argtypes = [vp] * 8
+        lib.moe_expert_ffn_bwd.argtypes = [vp] * 5 + [ctypes.POINTER(_Layout)] + [vp] * 9
+        lib.moe_dispatch_bwd.argtypes = [vp] * 5
+        lib.moe_gate_bwd.argtypes = [vp] * 6
+        _lib = lib
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, numel: int, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name}: need a contiguous device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"{name}: {t.numel()} elements, need {numel}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Layout:
+    """Device arrays of the send layout (see moe_layout_t)."""
+
+    def __init__(self, E: int, P: int, A: int, device):
+        i32 = dict(dtype=torch.int32, device=device)
+        self.slot_of_expert = torch.zeros(E, **i32)
+        self.slot_offsets = torch.zeros(E + 1, **i32)
+        self.dest_offsets = torch.zeros(P + 1, **i32)
+        self.dest_slots = torch.zeros(P + 1, **i32)
+        self.pos = torch.zeros(A, **i32)
+        self.perm = torch.zeros(A, **i32)
+        self.c = _Layout(*(t.data_ptr() for t in (self.slot_of_expert, self.slot_offsets, self.dest_offsets,
+                                                  self.dest_slots, self.pos, self.perm)))
+
+
+class Handle:
+    """A moe_handle_t plus its workspace.  Methods carry the names of the C entry points."""
+
+    def __init__(self, *, T: int, d: int, h: int, E: int, k: int, P: int, self_dest: int, G: int,
+                 dtype: str, act: str, renorm: int, device="cuda:0", alloc_workspace: bool = True):
+        self.lib = load()
+        self.shape = _Shape(T, d, h, E, k, P, self_dest, G, DTYPES[dtype], ACTS[act], renorm)
+        self.T, self.d, self.h, self.E, self.k, self.P, self.G = T, d, h, E, k, P, G
+        self.A = T * k
+        self.swiglu = act == "swiglu"
+        self.elt = TORCH_DTYPE[DTYPES[dtype]]
+        self.device = torch.device(device)
+        self._h = ctypes.c_void_p()
+        self._check(self.lib.moe_create(ctypes.byref(self._h), ctypes.byref(self.shape)), "moe_create")
+        n = ctypes.c_size_t()
+        self._check(self.lib.moe_workspace_bytes(self._h, ctypes.byref(n)), "moe_workspace_bytes")
+        self.workspace_bytes = n.value
+        self.ws = torch.empty(n.value, dtype=torch.uint8, device=self.device) if alloc_workspace else None
+
+    def close(self):
+        if self._h:
+            self.lib.moe_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int, where: str):
+        if rc != 0:
+            detail = self.lib.moe_status_string(rc).decode()
+            if rc == -7:
+                detail += f", hipError {self.lib.moe_last_hip_error()}"
+            raise MoeError(rc, where, detail)
+
+    def _ws(self) -> int:
+        if self.ws is None:
+            raise ValueError("no workspace attached")
+        return self.ws.data_ptr()
+
+    def new_layout(self) -> Layout:
+        return Layout(self.E, self.P, self.A, self.device)
+
+    # ---- the entry points ---------------------------------------------------------------
+    def read_status(self) -> int:
+        v = ctypes.c_int(0)
+        self._check(self.lib.moe_read_status(self._h, self._ws(), _stream(), ctypes.byref(v)), "moe_read_status")
+        return v.value
+
+    def gate_topk(self, X, Wg, bg, logits, idx, w):
+        f32, i32 = torch.float32, torch.int32
+        self._check(self.lib.moe_gate_topk(
+            self._h, _ptr(X, self.elt, self.T * self.d, "X"), _ptr(Wg, f32, self.d * self.E, "Wg"),
+            _ptr(bg, f32, self.E, "bg"), _ptr(logits, f32, self.T * self.E, "logits"),
+            _ptr(idx, i32, self.A, "idx"), _ptr(w, f32, self.A, "w"), _stream()), "moe_gate_topk")
+
+    def expert_counts(self, idx, counts):
+        i32 = torch.int32
+        self._check(self.lib.moe_expert_counts(self._h, _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"),
+                                               self._ws(), _stream()), "moe_expert_counts")
+
+    def dispatch(self, expert_dest, X, idx, counts, layout: Layout, Xp):
+        i32 = torch.int32
+        self._check(self.lib.moe_dispatch(
+            self._h, _ptr(expert_dest, i32, self.E, "expert_dest"), _ptr(X, self.elt, self.T * self.d, "X"),
+            _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"), ctypes.byref(layout.c),
+            _ptr(Xp, self.elt, self.A * self.d, "Xp"), self._ws(), _stream()), "moe_dispatch")
+
+    def expert_ffn_fwd(self, Xp, layout: Layout, W1, W2, W3, Yp, Z, U):
+        e, dh = self.elt, self.G * self.d * self.h
+        self._check(self.lib.moe_expert_ffn_fwd(
+            self._h, _ptr(Xp, e, self.A * self.d, "Xp"), ctypes.byref(layout.c), _ptr(W1, e, dh, "W1"), _ptr(W2, e, dh, "W2"),
+            _ptr(W3, e, dh, "W3"), _ptr(Yp, e, self.A * self.d, "Yp"), _ptr(Z, e, self.A * self.h, "Z"),
+            _ptr(U, e, self.A * self.h, "U"), self._ws(), _stream()), "moe_expert_ffn_fwd")
+
+    def combine(self, Yp, pos, w, out):
+        self._check(self.lib.moe_combine(
+            self._h, _ptr(Yp, self.elt, self.A * self.d, "Yp"), _ptr(pos, torch.int32, self.A, "pos"),
+            _ptr(w, torch.float32, self.A, "w"), _ptr(out, self.elt, self.T * self.d, "out"), _stream()), "moe_combine")
+
+    def combine_bwd(self, dOut, Yp, pos, w, dYp, dw):
+        e = self.elt
+        self._check(self.lib.moe_combine_bwd(
+            self._h, _ptr(dOut, e, self.T * self.d, "dOut"), _ptr(Yp, e, self.A * self.d, "Yp"),
+            _ptr(pos, torch.int32, self.A, "pos"), _ptr(w, torch.float32, self.A, "w"),
+            _ptr(dYp, e, self.A * self.d, "dYp"), _ptr(dw, torch.float32, self.A, "dw"), _stream()), "moe_combine_bwd")
+
+    def expert_ffn_bwd(self, dYp, Xp, Z, U, layout: Layout, W1, W2, W3, dXp, dW1, dW2, dW3):
+        e, f32, dh = self.elt, torch.float32, self.G * self.d * self.h
+        self._check(self.lib.moe_expert_ffn_bwd(
+            self._h, _ptr(dYp, e, self.A * self.d, "dYp"), _ptr(Xp, e, self.A * self.d, "Xp"),
+            _ptr(Z, e, self.A * self.h, "Z"), _ptr(U, e, self.A * self.h, "U"), ctypes.byref(layout.c),
+            _ptr(W1, e, dh, "W1"), _ptr(W2, e, dh, "W2"), _ptr(W3, e, dh, "W3"),
+            _ptr(dXp, e, self.A * self.d, "dXp"), _ptr(dW1, f32, dh, "dW1"), _ptr(dW2, f32, dh, "dW2"),
+            _ptr(dW3, f32, dh, "dW3"), self._ws(), _stream()), "moe_expert_ffn_bwd")
+
+    def dispatch_bwd(self, dXp, pos, dX):
+        self._check(self.lib.moe_dispatch_bwd(
+            self._h, _ptr(dXp, self.elt, self.A * self.d, "dXp"), _ptr(pos, torch.int32, self.A, "pos"),
+            _ptr(dX, self.elt, self.T * self.d, "dX"), _stream()), "moe_dispatch_bwd")
+
+    def gate_bwd(self, dw, logits, idx, dlogits):
+        f32 = torch.float32
+        self._check(self.lib.moe_gate_bwd(
+            self._h, _ptr(dw, f32, self.A, "dw"), _ptr(logits, f32, self.T * self.E, "logits"),
+            _ptr(idx, torch.int32, self.A, "idx"), _ptr(dlogits, f32, self.T * self.E, "dlogits"), _stream()), "moe_gate_bwd")
+
+
+class LayerBuffers:
+    """Every device buffer of one layer pass, allocated once (nothing is allocated per step)."""
+
+    def __init__(self, hd: Handle, backward: bool):
+        dev, e = hd.device, hd.elt
+        f32 = dict(dtype=torch.float32, device=dev)
+        i32 = dict(dtype=torch.int32, device=dev)
+        T, d, h, E, A, G = hd.T, hd.d, hd.h, hd.E, hd.A, hd.G
+        self.logits = torch.empty(T, E, **f32)
+        self.idx = torch.empty(T, hd.k, **i32)
+        self.w = torch.empty(T, hd.k, **f32)
+        self.counts = torch.empty(E, **i32)
+        self.layout = hd.new_layout()
+        self.Xp = torch.empty(A, d, dtype=e, device=dev)
+        self.Yp = torch.empty(A, d, dtype=e, device=dev)
+        self.Z = torch.empty(A, h, dtype=e, device=dev)
+        self.U = torch.empty(A, h, dtype=e, device=dev) if hd.swiglu else None
+        self.out = torch.empty(T, d, dtype=e, device=dev)
+        if backward:
+            self.dYp = torch.empty(A, d, dtype=e, device=dev)
+            self.dw = torch.empty(T, hd.k, **f32)
+            self.dXp = torch.empty(A, d, dtype=e, device=dev)
+            self.dW1 = torch.empty(G, d, h, **f32)
+            self.dW2 = torch.empty(G, h, d, **f32)
+            self.dW3 = torch.empty(G, d, h, **f32) if hd.swiglu else None
+            self.dX = torch.empty(T, d, dtype=e, device=dev)
+            self.dlogits = torch.empty(T, E, **f32)
+
+
+def layer_forward(hd: Handle, b: LayerBuffers, X, Wg, bg, expert_dest, W1, W2, W3):
+    """The forward calls in order; rows of other destinations in b.Yp are left as the caller set them."""
+    hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w)
+    hd.expert_counts(b.idx, b.counts)
+    hd.dispatch(expert_dest, X, b.idx, b.counts, b.layout, b.Xp)
+    hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z, b.U)
+    hd.combine(b.Yp, b.layout.pos, b.w, b.out)
+
+
+def layer_backward(hd: Handle, b: LayerBuffers, dOut, W1, W2, W3):
+    """The backward calls in order; rows of other destinations in b.dXp are left as the caller set them."""
+    hd.combine_bwd(dOut, b.Yp, b.layout.pos, b.w, b.dYp, b.dw)
+    hd.expert_ffn_bwd(b.dYp, b.Xp, b.Z, b.U, b.layout, W1, W2, W3, b.dXp, b.dW1, b.dW2, b.dW3)
+    hd.dispatch_bwd(b.dXp, b.layout.pos, b.dX)
+    hd.gate_bwd(b.dw, b.logits, b.idx, b.dlogits)

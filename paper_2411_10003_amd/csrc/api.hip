@@ -1,0 +1,220 @@
+// Host side of the C ABI: argument checks, workspace carving and kernel sequencing.
+// Nothing here synchronises or allocates device memory (moe_read_status excepted).
+#include "internal.h"
+
+#include <new>
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+inline int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return MOE_OK;
+    g_last_hip_error = (int)e;
+    return MOE_ERR_HIP;
+}
+
+inline size_t elt_size(const moe_shape_t& s) { return s.dtype == MOE_BF16 ? 2 : 4; }
+
+int check_shape(const moe_shape_t& s)
+{
+    if (s.dtype != MOE_F32 && s.dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (s.act != MOE_ACT_GELU && s.act != MOE_ACT_SWIGLU) return MOE_ERR_SHAPE;
+    if (s.T < 1 || s.d < 1 || s.h < 1) return MOE_ERR_SHAPE;
+    if (s.k < 1 || s.k > 8 || s.E < s.k || s.E > 1024) return MOE_ERR_SHAPE;
+    if (s.P < 1 || s.P > s.E || s.self < 0 || s.self >= s.P) return MOE_ERR_SHAPE;
+    if (s.G < 1 || s.G > s.E) return MOE_ERR_SHAPE;
+    if (s.renorm != 0 && s.renorm != 1) return MOE_ERR_SHAPE;
+    if ((long long)s.T * s.k >= (1ll << 31) / 2) return MOE_ERR_SHAPE;
+    if (s.dtype == MOE_BF16 && (s.d % 64 != 0 || s.h % 64 != 0)) return MOE_ERR_SHAPE;
+    if (s.dtype == MOE_F32 && (s.d % 4 != 0)) return MOE_ERR_SHAPE;
+    if (s.dtype == MOE_F32 && (long long)s.T * s.k > 16ll * 65535) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255) != 0; }
+
+struct Carve {
+    char* base;
+    const moe_ctx* c;
+    int32_t* status() const { return reinterpret_cast<int32_t*>(base + c->off_status); }
+    int32_t* chunk_hist() const { return reinterpret_cast<int32_t*>(base + c->off_chunk_hist); }
+    int32_t* chunk_base() const { return reinterpret_cast<int32_t*>(base + c->off_chunk_base); }
+    void* act() const { return base + c->off_act; }
+    void* dz() const { return base + c->off_dz; }
+    void* du() const { return base + c->off_du; }
+};
+
+}  // namespace
+
+extern "C" {
+
+int moe_create(moe_handle_t* out, const moe_shape_t* shape)
+{
+    if (!out || !shape) return MOE_ERR_NULL;
+    const int rc = check_shape(*shape);
+    if (rc != MOE_OK) return rc;
+    moe_ctx* c = new (std::nothrow) moe_ctx();
+    if (!c) return MOE_ERR_NULL;
+    c->s = *shape;
+    const size_t A = (size_t)shape->T * shape->k;
+    c->n_chunks = (int)((A + ROUTE_CHUNK - 1) / ROUTE_CHUNK);
+    size_t off = 0;
+    c->off_status = off;      off += 256;
+    c->off_chunk_hist = off;  off += align256((size_t)c->n_chunks * shape->E * sizeof(int32_t));
+    c->off_chunk_base = off;  off += align256((size_t)c->n_chunks * shape->E * sizeof(int32_t));
+    const size_t ah = align256(A * shape->h * elt_size(*shape));
+    c->off_act = off;         off += ah;
+    c->off_dz = off;          off += ah;
+    c->off_du = off;          off += (shape->act == MOE_ACT_SWIGLU) ? ah : 0;
+    c->ws_bytes = off;
+    *out = c;
+    return MOE_OK;
+}
+
+int moe_destroy(moe_handle_t h)
+{
+    if (!h) return MOE_ERR_NULL;
+    delete h;
+    return MOE_OK;
+}
+
+int moe_workspace_bytes(moe_handle_t h, size_t* bytes)
+{
+    if (!h || !bytes) return MOE_ERR_NULL;
+    *bytes = h->ws_bytes;
+    return MOE_OK;
+}
+
+const char* moe_status_string(int status)
+{
+    switch (status) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "null pointer";
+        case MOE_ERR_SHAPE: return "unsupported or inconsistent shape";
+        case MOE_ERR_PLAN: return "expert placement out of range";
+        case MOE_ERR_WORKSPACE: return "workspace missing or misaligned";
+        case MOE_ERR_DTYPE: return "unsupported dtype";
+        case MOE_ERR_UNIMPLEMENTED: return "not implemented";
+        case MOE_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+int moe_last_hip_error(void) { return g_last_hip_error; }
+
+int moe_read_status(moe_handle_t h, const void* ws, void* stream, int* status)
+{
+    if (!h || !status) return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    int32_t v = 0;
+    hipError_t e = hipMemcpyAsync(&v, (const char*)ws + h->off_status, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_status(e);
+    *status = (int)v;
+    return MOE_OK;
+}
+
+int moe_gate_topk(moe_handle_t h, const void* X, const float* Wg, const float* bg,
+                  float* logits, int32_t* idx, float* w, void* stream)
+{
+    if (!h || !X || !Wg || !bg || !logits || !idx || !w) return MOE_ERR_NULL;
+    return hip_status(launch_gate_topk(h->s, X, Wg, bg, logits, idx, w, (hipStream_t)stream));
+}
+
+int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void* ws, void* stream)
+{
+    if (!h || !idx || !counts) return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    const Carve c{(char*)ws, h};
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
+    if (e == hipSuccess) e = launch_counts_from_hist(h->s, c.chunk_hist(), h->n_chunks, counts, st);
+    return hip_status(e);
+}
+
+int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                 const int32_t* counts, const moe_layout_t* L, void* Xp, void* ws, void* stream)
+{
+    if (!h || !expert_dest || !X || !idx || !counts || !L || !Xp) return MOE_ERR_NULL;
+    if (!L->slot_of_expert || !L->slot_offsets || !L->dest_offsets || !L->dest_slots || !L->pos || !L->perm)
+        return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    const Carve c{(char*)ws, h};
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
+    if (e == hipSuccess)
+        e = launch_layout_scan(h->s, expert_dest, counts, c.chunk_hist(), c.chunk_base(), h->n_chunks, *L, c.status(), st);
+    if (e == hipSuccess) e = launch_positions(h->s, idx, c.chunk_base(), h->n_chunks, *L, st);
+    if (e == hipSuccess) e = launch_scatter_rows(h->s, X, L->pos, Xp, st);
+    return hip_status(e);
+}
+
+int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* L,
+                       const void* W1, const void* W2, const void* W3,
+                       void* Yp, void* Z, void* U, void* ws, void* stream)
+{
+    if (!h || !Xp || !L || !W1 || !W2 || !Yp || !Z) return MOE_ERR_NULL;
+    if (!L->slot_offsets || !L->dest_slots) return MOE_ERR_NULL;
+    const bool swiglu = h->s.act == MOE_ACT_SWIGLU;
+    if (swiglu && (!W3 || !U)) return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    const Carve c{(char*)ws, h};
+    ffn_args a{};
+    a.Xp = Xp; a.W1 = W1; a.W2 = W2; a.W3 = W3;
+    a.slot_offsets = L->slot_offsets; a.dest_slots = L->dest_slots;
+    a.Yp = Yp; a.Z = Z; a.U = U; a.Act = c.act();
+    hipStream_t st = (hipStream_t)stream;
+    return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_fwd_f32(h->s, a, st) : launch_ffn_fwd_bf16(h->s, a, st));
+}
+
+int moe_combine(moe_handle_t h, const void* Yp, const int32_t* pos, const float* w, void* out, void* stream)
+{
+    if (!h || !Yp || !pos || !w || !out) return MOE_ERR_NULL;
+    return hip_status(launch_combine(h->s, Yp, pos, w, out, (hipStream_t)stream));
+}
+
+int moe_combine_bwd(moe_handle_t h, const void* dOut, const void* Yp, const int32_t* pos, const float* w,
+                    void* dYp, float* dw, void* stream)
+{
+    if (!h || !dOut || !Yp || !pos || !w || !dYp || !dw) return MOE_ERR_NULL;
+    return hip_status(launch_combine_bwd(h->s, dOut, Yp, pos, w, dYp, dw, (hipStream_t)stream));
+}
+
+int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                       const moe_layout_t* L, const void* W1, const void* W2, const void* W3,
+                       void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream)
+{
+    if (!h || !dYp || !Xp || !Z || !L || !W1 || !W2 || !dXp || !dW1 || !dW2) return MOE_ERR_NULL;
+    if (!L->slot_offsets || !L->dest_slots) return MOE_ERR_NULL;
+    const bool swiglu = h->s.act == MOE_ACT_SWIGLU;
+    if (swiglu && (!W3 || !U || !dW3)) return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    const Carve c{(char*)ws, h};
+    ffn_args a{};
+    a.Xp = Xp; a.W1 = W1; a.W2 = W2; a.W3 = W3;
+    a.slot_offsets = L->slot_offsets; a.dest_slots = L->dest_slots;
+    a.Z = const_cast<void*>(Z); a.U = const_cast<void*>(U); a.Act = c.act();
+    a.dYp = dYp; a.dXp = dXp; a.dZ = c.dz(); a.dU = c.du();
+    a.dW1 = dW1; a.dW2 = dW2; a.dW3 = dW3;
+    hipStream_t st = (hipStream_t)stream;
+    return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_bwd_f32(h->s, a, st) : launch_ffn_bwd_bf16(h->s, a, st));
+}
+
+int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* dX, void* stream)
+{
+    if (!h || !dXp || !pos || !dX) return MOE_ERR_NULL;
+    return hip_status(launch_dispatch_bwd(h->s, dXp, pos, dX, (hipStream_t)stream));
+}
+
+int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int32_t* idx,
+                 float* dlogits, void* stream)
+{
+    if (!h || !dw || !logits || !idx || !dlogits) return MOE_ERR_NULL;
+    return hip_status(launch_gate_bwd(h->s, dw, logits, idx, dlogits, (hipStream_t)stream));
+}
+
+}  // extern "C"

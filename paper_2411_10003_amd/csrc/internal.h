@@ -1,0 +1,80 @@
+// Internal declarations shared by the translation units of libmoehot (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/moehot.h"
+
+struct moe_ctx {
+    moe_shape_t s;
+    // workspace layout (byte offsets, all multiples of 256)
+    size_t off_status;     // int32 status word(s)
+    size_t off_chunk_hist; // int32 [n_chunks][E] per-chunk expert histograms
+    size_t off_chunk_base; // int32 [n_chunks][E] exclusive prefix over chunks
+    size_t off_act;        // elt [A,h]  activation output A (forward) / recomputed A (backward)
+    size_t off_dz;         // elt [A,h]  dZ
+    size_t off_du;         // elt [A,h]  dU (SwiGLU)
+    size_t ws_bytes;
+    int n_chunks;          // ceil(A / ROUTE_CHUNK)
+};
+
+// Assignments handled by one wave of the routing kernels.
+constexpr int ROUTE_CHUNK = 256;
+
+typedef uint16_t bf16_t;  // storage only
+
+// ---- launchers (each returns a hipError_t; they enqueue on `st`) ----------------------------
+hipError_t launch_gate_topk(const moe_shape_t& s, const void* X, const float* Wg, const float* bg,
+                            float* logits, int32_t* idx, float* w, hipStream_t st);
+hipError_t launch_gate_bwd(const moe_shape_t& s, const float* dw, const float* logits, const int32_t* idx,
+                           float* dlogits, hipStream_t st);
+
+hipError_t launch_chunk_hist(const moe_shape_t& s, const int32_t* idx, int32_t* chunk_hist, int n_chunks, hipStream_t st);
+hipError_t launch_counts_from_hist(const moe_shape_t& s, const int32_t* chunk_hist, int n_chunks, int32_t* counts, hipStream_t st);
+hipError_t launch_layout_scan(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* counts,
+                              const int32_t* chunk_hist, int32_t* chunk_base, int n_chunks,
+                              const moe_layout_t& L, int32_t* status, hipStream_t st);
+hipError_t launch_positions(const moe_shape_t& s, const int32_t* idx, const int32_t* chunk_base, int n_chunks,
+                            const moe_layout_t& L, hipStream_t st);
+
+hipError_t launch_scatter_rows(const moe_shape_t& s, const void* X, const int32_t* pos, void* Xp, hipStream_t st);
+hipError_t launch_combine(const moe_shape_t& s, const void* Yp, const int32_t* pos, const float* w, void* out, hipStream_t st);
+hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void* Yp, const int32_t* pos,
+                              const float* w, void* dYp, float* dw, hipStream_t st);
+hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
+
+struct ffn_args {
+    const void *Xp, *W1, *W2, *W3;
+    const int32_t *slot_offsets, *dest_slots;
+    void *Yp, *Z, *U, *Act;            // forward outputs (Act in workspace)
+    const void* dYp;                   // backward
+    void *dXp, *dZ, *dU;               // dZ, dU in workspace
+    float *dW1, *dW2, *dW3;
+};
+hipError_t launch_ffn_fwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
+hipError_t launch_ffn_bwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
+hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
+hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
+
+// ---- small device helpers ----------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Group table of the hosted slots, rebuilt by every FFN block from the layout (G is small).
+__device__ __forceinline__ void hosted_range(const int32_t* dest_slots, int self, int Gcap, int& first_slot, int& n_groups) {
+    first_slot = dest_slots[self];
+    int n = dest_slots[self + 1] - first_slot;
+    n_groups = n < Gcap ? n : Gcap;
+    if (n_groups < 0) n_groups = 0;
+}

@@ -1,0 +1,256 @@
+// Row movers bound by HBM bandwidth: the send buffer of the first all-to-all (dispatch), the
+// weighted return after the second one (combine), and their gradients (Fig. 2 of the paper and
+// the two backward all-to-alls of its performance model, Section 4.2).
+//
+// One wavefront owns one token.  A token's row is read once and written to its k send rows
+// (scatter form of Xp[r] = X[perm[r]/k]), so traffic is the algorithmic minimum
+// (1 + k) * T * d elements.  Lanes move 16 bytes per access.
+#include "internal.h"
+
+namespace {
+
+constexpr int ROW_WAVES = 4;   // tokens per block
+constexpr int MAXK = 8;
+
+template <typename ET> struct Vec;                      // 16-byte vector of elements
+template <> struct Vec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* f) {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+template <> struct Vec<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ uint4 pack(const float* f) {
+        return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+    }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Xp[pos[t*k+j], :] = X[t, :]
+template <typename ET>
+__global__ __launch_bounds__(ROW_WAVES * 64) void scatter_rows_kernel(
+    const ET* __restrict__ X, const int32_t* __restrict__ pos, ET* __restrict__ Xp, int T, int d, int k)
+{
+    constexpr int VN = Vec<ET>::N;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4* src = reinterpret_cast<const uint4*>(X + (size_t)t * d);
+    const int nv = d / VN;
+    for (int j = 0; j < k; ++j) {
+        // the row is re-read from cache for j > 0; HBM sees it once
+        uint4* dst = reinterpret_cast<uint4*>(Xp + (size_t)pos[(size_t)t * k + j] * d);
+#pragma unroll 4
+        for (int v = lane; v < nv; v += 64) dst[v] = src[v];
+    }
+}
+
+// K-specialised variant: every 16-byte piece is loaded once and stored K times.
+template <typename ET, int K>
+__global__ __launch_bounds__(ROW_WAVES * 64) void scatter_rows_k_kernel(
+    const ET* __restrict__ X, const int32_t* __restrict__ pos, ET* __restrict__ Xp, int T, int d)
+{
+    constexpr int VN = Vec<ET>::N;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4* src = reinterpret_cast<const uint4*>(X + (size_t)t * d);
+    uint4* dst[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) dst[j] = reinterpret_cast<uint4*>(Xp + (size_t)pos[(size_t)t * K + j] * d);
+    const int nv = d / VN;
+#pragma unroll 4
+    for (int v = lane; v < nv; v += 64) {
+        const uint4 x = src[v];
+#pragma unroll
+        for (int j = 0; j < K; ++j) dst[j][v] = x;
+    }
+}
+
+// out[t,:] = sum_j w[t,j] * Yp[pos[t*k+j],:]   (fp32, ascending j, one rounding)
+template <typename ET>
+__global__ __launch_bounds__(ROW_WAVES * 64) void combine_kernel(
+    const ET* __restrict__ Yp, const int32_t* __restrict__ pos, const float* __restrict__ w,
+    ET* __restrict__ out, int T, int d, int k)
+{
+    constexpr int VN = Vec<ET>::N;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4* src[MAXK];
+    float wj[MAXK];
+#pragma unroll
+    for (int j = 0; j < MAXK; ++j) {
+        if (j < k) {
+            src[j] = reinterpret_cast<const uint4*>(Yp + (size_t)pos[(size_t)t * k + j] * d);
+            wj[j] = w[(size_t)t * k + j];
+        }
+    }
+    uint4* dst = reinterpret_cast<uint4*>(out + (size_t)t * d);
+    const int nv = d / VN;
+    for (int v = lane; v < nv; v += 64) {
+        float acc[VN];
+#pragma unroll
+        for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < MAXK; ++j) {
+            if (j < k) {
+                float y[VN];
+                Vec<ET>::unpack(src[j][v], y);
+#pragma unroll
+                for (int i = 0; i < VN; ++i) acc[i] = fmaf(wj[j], y[i], acc[i]);
+            }
+        }
+        dst[v] = Vec<ET>::pack(acc);
+    }
+}
+
+// dYp[pos[a],:] = w[a] * dOut[t,:] ;  dw[t,j] = <dOut[t,:], Yp[pos[a],:]>
+template <typename ET>
+__global__ __launch_bounds__(ROW_WAVES * 64) void combine_bwd_kernel(
+    const ET* __restrict__ dOut, const ET* __restrict__ Yp, const int32_t* __restrict__ pos,
+    const float* __restrict__ w, ET* __restrict__ dYp, float* __restrict__ dw, int T, int d, int k)
+{
+    constexpr int VN = Vec<ET>::N;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4* ysrc[MAXK];
+    uint4* gdst[MAXK];
+    float wj[MAXK], dot[MAXK];
+#pragma unroll
+    for (int j = 0; j < MAXK; ++j) {
+        dot[j] = 0.0f;
+        if (j < k) {
+            const size_t row = (size_t)pos[(size_t)t * k + j];
+            ysrc[j] = reinterpret_cast<const uint4*>(Yp + row * d);
+            gdst[j] = reinterpret_cast<uint4*>(dYp + row * d);
+            wj[j] = w[(size_t)t * k + j];
+        }
+    }
+    const uint4* gsrc = reinterpret_cast<const uint4*>(dOut + (size_t)t * d);
+    const int nv = d / VN;
+    for (int v = lane; v < nv; v += 64) {
+        float g[VN];
+        Vec<ET>::unpack(gsrc[v], g);
+#pragma unroll
+        for (int j = 0; j < MAXK; ++j) {
+            if (j < k) {
+                float y[VN], o[VN];
+                Vec<ET>::unpack(ysrc[j][v], y);
+#pragma unroll
+                for (int i = 0; i < VN; ++i) { dot[j] = fmaf(g[i], y[i], dot[j]); o[i] = wj[j] * g[i]; }
+                gdst[j][v] = Vec<ET>::pack(o);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < MAXK; ++j) {
+        if (j < k) {
+            const float s = wave_sum(dot[j]);
+            if (lane == 0) dw[(size_t)t * k + j] = s;
+        }
+    }
+}
+
+// dX[t,:] = sum_j dXp[pos[t*k+j],:]
+template <typename ET>
+__global__ __launch_bounds__(ROW_WAVES * 64) void dispatch_bwd_kernel(
+    const ET* __restrict__ dXp, const int32_t* __restrict__ pos, ET* __restrict__ dX, int T, int d, int k)
+{
+    constexpr int VN = Vec<ET>::N;
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const uint4* src[MAXK];
+#pragma unroll
+    for (int j = 0; j < MAXK; ++j)
+        if (j < k) src[j] = reinterpret_cast<const uint4*>(dXp + (size_t)pos[(size_t)t * k + j] * d);
+    uint4* dst = reinterpret_cast<uint4*>(dX + (size_t)t * d);
+    const int nv = d / VN;
+    for (int v = lane; v < nv; v += 64) {
+        float acc[VN];
+#pragma unroll
+        for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < MAXK; ++j) {
+            if (j < k) {
+                float y[VN];
+                Vec<ET>::unpack(src[j][v], y);
+#pragma unroll
+                for (int i = 0; i < VN; ++i) acc[i] += y[i];
+            }
+        }
+        dst[v] = Vec<ET>::pack(acc);
+    }
+}
+
+inline dim3 row_grid(int T) { return dim3((T + ROW_WAVES - 1) / ROW_WAVES); }
+
+}  // namespace
+
+hipError_t launch_scatter_rows(const moe_shape_t& s, const void* X, const int32_t* pos, void* Xp, hipStream_t st)
+{
+    if (s.T == 0) return hipSuccess;
+    const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
+    if (s.dtype == MOE_F32) {
+        hipLaunchKernelGGL(scatter_rows_kernel<float>, g, b, 0, st, (const float*)X, pos, (float*)Xp, s.T, s.d, s.k);
+    } else if (s.k == 1) {
+        hipLaunchKernelGGL((scatter_rows_k_kernel<bf16_t, 1>), g, b, 0, st, (const bf16_t*)X, pos, (bf16_t*)Xp, s.T, s.d);
+    } else if (s.k == 2) {
+        hipLaunchKernelGGL((scatter_rows_k_kernel<bf16_t, 2>), g, b, 0, st, (const bf16_t*)X, pos, (bf16_t*)Xp, s.T, s.d);
+    } else {
+        hipLaunchKernelGGL(scatter_rows_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)X, pos, (bf16_t*)Xp, s.T, s.d, s.k);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_combine(const moe_shape_t& s, const void* Yp, const int32_t* pos, const float* w, void* out, hipStream_t st)
+{
+    if (s.T == 0) return hipSuccess;
+    const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
+    if (s.dtype == MOE_F32)
+        hipLaunchKernelGGL(combine_kernel<float>, g, b, 0, st, (const float*)Yp, pos, w, (float*)out, s.T, s.d, s.k);
+    else
+        hipLaunchKernelGGL(combine_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)Yp, pos, w, (bf16_t*)out, s.T, s.d, s.k);
+    return hipGetLastError();
+}
+
+hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void* Yp, const int32_t* pos,
+                              const float* w, void* dYp, float* dw, hipStream_t st)
+{
+    if (s.T == 0) return hipSuccess;
+    const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
+    if (s.dtype == MOE_F32)
+        hipLaunchKernelGGL(combine_bwd_kernel<float>, g, b, 0, st, (const float*)dOut, (const float*)Yp, pos, w,
+                           (float*)dYp, dw, s.T, s.d, s.k);
+    else
+        hipLaunchKernelGGL(combine_bwd_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)dOut, (const bf16_t*)Yp, pos, w,
+                           (bf16_t*)dYp, dw, s.T, s.d, s.k);
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st)
+{
+    if (s.T == 0) return hipSuccess;
+    const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
+    if (s.dtype == MOE_F32)
+        hipLaunchKernelGGL(dispatch_bwd_kernel<float>, g, b, 0, st, (const float*)dXp, pos, (float*)dX, s.T, s.d, s.k);
+    else
+        hipLaunchKernelGGL(dispatch_bwd_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
+    return hipGetLastError();
+}

@@ -1,0 +1,61 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every entry point the
+header declares, and rejects bad shapes before anything could be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moehot.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2411_10003_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2411_10003_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2411_10003_amd import binding
+    names = _declared()
+    assert len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_create_validates_shapes(lib):
+    from paper_2411_10003_amd.binding import _Shape
+    good = dict(T=64, d=64, h=128, E=8, k=2, P=4, self=0, G=2, dtype=1, act=0, renorm=1)
+
+    def create(**kw):
+        f = dict(good)
+        f.update(kw)
+        s = _Shape(*(f[n] for n, _ in _Shape._fields_))
+        h = ctypes.c_void_p()
+        rc = lib.moe_create(ctypes.byref(h), ctypes.byref(s))
+        if rc == 0:
+            n = ctypes.c_size_t()
+            assert lib.moe_workspace_bytes(h, ctypes.byref(n)) == 0 and n.value % 256 == 0 and n.value > 0
+            assert lib.moe_destroy(h) == 0
+        return rc
+
+    assert create() == 0
+    assert create(dtype=0, d=36) == 0
+    assert create(k=0) == -2 and create(k=9) == -2 and create(E=1) == -2
+    assert create(d=100) == -2 and create(h=100) == -2            # bf16 needs multiples of 64
+    assert create(dtype=0, d=34) == -2
+    assert create(P=9) == -2 and create(self=4) == -2 and create(G=0) == -2 and create(G=9) == -2
+    assert create(dtype=7) == -5 and create(act=3) == -2 and create(renorm=2) == -2
+    assert create(T=0) == -2
+    assert lib.moe_create(None, None) == -1
+    assert lib.moe_status_string(-3).decode() == "expert placement out of range"
