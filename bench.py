@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic tokens already resident in HBM:
+gate+top-k, expert counts, placement-aware dispatch, grouped expert FFN, combine, and for the
+configurations with a backward pass combine_bwd, FFN backward, dispatch_bwd and gate_bwd.
+Prints one JSON line: tokens/s, the roofline of the grouped FFN kernel (bf16 MFMA) measured with
+events on the launch stream, per-call times with their HBM fractions, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "MoE-layer tokens/sec/GPU (gate+dispatch+grouped FFN+combine); FFN MFMA util"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3        # fp32 vector
+PEAK_HBM_GBS = 8000.0          # HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, inp, expert_dest, n_tokens: int, n_hidden: int):
+    """The oracle as it stands on the first n_tokens tokens of the workload: the whole layer pass,
+    weight gradients on n_hidden hidden units per group with their time scaled to all h."""
+    from oracle import moe_oracle as orc
+    from paper_2411_10003_amd import workload as wl
+    orc.build()
+    k, act = cfg.k, cfg.act
+    X = inp["X"][:n_tokens]
+    t0 = time.perf_counter()
+    r = orc.route(X, inp["Wg"], inp["bg"], k, cfg.renorm)
+    lay = orc.place(r["idx"], r["counts"], expert_dest, cfg.P)
+    goe = wl.group_of_expert(expert_dest, cfg.self_dest)
+    idx = r["idx"].reshape(-1)
+    hosted = orc.hosted_assignments(idx, goe)
+    Xp = orc.dispatch(X, lay["perm"], k)
+    Y = orc.ffn_fwd(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, hosted)
+    Yp = inp["Yp_fill"][: n_tokens * k].astype(np.float64)
+    Yp[lay["pos"][hosted]] = Y
+    out = orc.combine(Yp, lay["pos"], r["w"], k)
+    t_rows = time.perf_counter() - t0
+    t_w = 0.0
+    if cfg.backward:
+        t0 = time.perf_counter()
+        dOut = inp["dOut"][:n_tokens]
+        dYp, dw = orc.combine_bwd(dOut, Yp, lay["pos"], r["w"], k)
+        dXh = orc.ffn_bwd_rows(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, hosted, dYp[lay["pos"][hosted]])
+        dXp = inp["dXp_fill"][: n_tokens * k].astype(np.float64)
+        dXp[lay["pos"][hosted]] = dXh
+        orc.dispatch_bwd(dXp, lay["pos"], k)
+        orc.gate_bwd(dw, r["logits"], r["idx"], cfg.renorm)
+        t_rows += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        dYa = dYp[lay["pos"]].astype(np.float32)
+        G = int((np.asarray(expert_dest) == cfg.self_dest).sum())
+        for g in range(G):
+            for j in range(n_hidden):
+                orc.ffn_bwd_hidden(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, dYa, g, j)
+        t_w = (time.perf_counter() - t0) * (cfg.h / n_hidden)
+    total = t_rows + t_w
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": n_tokens / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": (f"first {n_tokens} of {cfg.T} tokens, whole layer pass in {total:.1f} s "
+                   f"(rows {t_rows:.1f} s; weight gradients on {n_hidden} of {cfg.h} hidden units per group, "
+                   f"scaled to {t_w:.1f} s)") if cfg.backward else
+                  f"first {n_tokens} of {cfg.T} tokens, whole forward pass in {total:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: the roofline target)")
+    ap.add_argument("--iteration", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build is one GPU's share of the layer; it has no multi-GPU path (use --gpus 1)")
+
+    import torch
+    from paper_2411_10003_amd import binding
+    from paper_2411_10003_amd import workload as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU")
+    binding.load()
+    cfg = wl.CONFIGS[args.config]
+    dev = "cuda:0"
+    dt = cfg.dtype
+
+    t0 = time.perf_counter()
+    inp = wl.make_inputs(cfg, args.iteration)
+    log(f"[bench] {cfg.name}: inputs drawn in {time.perf_counter() - t0:.1f} s")
+
+    def up(a, dtype="f32"):
+        t = torch.from_numpy(a)
+        return (t.to(torch.bfloat16) if dtype == "bf16" else t).to(dev)
+
+    X, Wg, bg = up(inp["X"], dt), up(inp["Wg"]), up(inp["bg"])
+    W1, W2 = up(inp["W1"], dt), up(inp["W2"], dt)
+    W3 = up(inp["W3"], dt) if cfg.act == "swiglu" else None
+    dOut = up(inp["dOut"], dt) if cfg.backward else None
+
+    hd = binding.Handle(T=cfg.T, d=cfg.d, h=cfg.h, E=cfg.E, k=cfg.k, P=cfg.P, self_dest=cfg.self_dest,
+                        G=cfg.G_max, dtype=dt, act=cfg.act, renorm=cfg.renorm, device=dev)
+    b = binding.LayerBuffers(hd, cfg.backward)
+    b.Yp.copy_(up(inp["Yp_fill"], dt))
+    if cfg.backward:
+        b.dXp.copy_(up(inp["dXp_fill"], dt))
+
+    # the plan is an input of the step: built once from this batch's input distribution
+    hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w)
+    hd.expert_counts(b.idx, b.counts)
+    counts = b.counts.cpu().numpy()
+    expert_dest_np = wl.make_plan(cfg, counts, threshold=(cfg.index == 4))
+    expert_dest = torch.from_numpy(expert_dest_np).to(dev)
+
+    calls = ["gate_topk", "expert_counts", "dispatch", "expert_ffn_fwd", "combine"]
+    if cfg.backward:
+        calls += ["combine_bwd", "expert_ffn_bwd", "dispatch_bwd", "gate_bwd"]
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w); mark(1)
+        hd.expert_counts(b.idx, b.counts); mark(2)
+        hd.dispatch(expert_dest, X, b.idx, b.counts, b.layout, b.Xp); mark(3)
+        hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z, b.U); mark(4)
+        hd.combine(b.Yp, b.layout.pos, b.w, b.out); mark(5)
+        if cfg.backward:
+            hd.combine_bwd(dOut, b.Yp, b.layout.pos, b.w, b.dYp, b.dw); mark(6)
+            hd.expert_ffn_bwd(b.dYp, b.Xp, b.Z, b.U, b.layout, W1, W2, W3, b.dXp, b.dW1, b.dW2, b.dW3); mark(7)
+            hd.dispatch_bwd(b.dXp, b.layout.pos, b.dX); mark(8)
+            hd.gate_bwd(b.dw, b.logits, b.idx, b.dlogits); mark(9)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert hd.read_status() == 0, "plan rejected"
+    do = b.layout.dest_offsets.cpu().numpy()
+    M = int(do[cfg.self_dest + 1] - do[cfg.self_dest])
+    so = b.layout.slot_offsets.cpu().numpy()
+    ds = b.layout.dest_slots.cpu().numpy()
+    group_rows = [int(so[s + 1] - so[s]) for s in range(ds[cfg.self_dest], ds[cfg.self_dest + 1])]
+    share = np.sort(counts)[::-1] / counts.sum()
+    log(f"[bench] counts per expert {counts.tolist()}  balance degree (std) {wl.balance_degree(counts):.1f}")
+    log(f"[bench] top-3 experts hold {share[:3].sum():.1%}, bottom-3 {share[-3:].sum():.1%}; "
+        f"hosted rows M={M} of A={cfg.A}; rows per hosted group {group_rows}")
+
+    n_ev = len(calls) + 1
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    call_ms = {c: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
+               for i, c in enumerate(calls)}
+
+    # algorithmic work
+    es = 2 if dt == "bf16" else 4
+    T, d, h, A, E, k = cfg.T, cfg.d, cfg.h, cfg.A, cfg.E, cfg.k
+    fwd_flops = 2.0 * M * d * h * cfg.n_mats
+    ffn_flops = fwd_flops * (3 if cfg.backward else 1)
+    ffn_ms = call_ms["expert_ffn_fwd"] + call_ms.get("expert_ffn_bwd", 0.0)
+    peak = PEAK_BF16_TFLOPS if dt == "bf16" else PEAK_F32_TFLOPS
+    achieved = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    hbm_bytes = {
+        "gate_topk": T * d * es + T * E * 4 + 8 * T * k,
+        "dispatch": (1 + k) * T * d * es,
+        "combine": (1 + k) * T * d * es,
+        "combine_bwd": (T * d + 2 * A * d) * es,
+        "dispatch_bwd": (1 + k) * T * d * es,
+    }
+    per_call = {}
+    for c in calls:
+        e = {"ms": round(call_ms[c], 4)}
+        if c in hbm_bytes:
+            gbs = hbm_bytes[c] / (call_ms[c] * 1e-3) / 1e9
+            e.update({"GB/s": round(gbs, 1), "hbm_frac": round(gbs / PEAK_HBM_GBS, 4)})
+        if c == "expert_ffn_fwd":
+            e.update({"TFLOP/s": round(fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
+        if c == "expert_ffn_bwd":
+            e.update({"TFLOP/s": round(2 * fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
+        per_call[c] = e
+
+    result = {
+        "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: T={T} d={d} h={h} {cfg.act} E={E} k={k} P={cfg.P} "
+                               f"hosted groups={len(group_rows)} alpha={wl.alpha_for(cfg, args.iteration)}",
+                   "pass": "fwd+bwd" if cfg.backward else "fwd", "hosted_rows_M": M, "assignments_A": A},
+        "roofline": {"bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "kernel": "grouped_gemm_kernel (all launches of expert_ffn_fwd/bwd in a step)",
+                     "flops_per_step": ffn_flops, "ms_per_step": ffn_ms},
+        "per_call": per_call,
+    }
+    if not args.no_cpu_baseline:
+        n_tok = args.cpu_tokens or {0: 512, 1: 1024, 2: 256, 3: 512, 4: 256}[cfg.index]
+        n_hid = {0: cfg.h, 1: 64, 2: 32, 3: 64, 4: 32}[cfg.index]
+        t0 = time.perf_counter()
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, expert_dest_np, min(n_tok, T), min(n_hid, h))
+        log(f"[bench] cpu baseline took {time.perf_counter() - t0:.1f} s")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
