@@ -11,11 +11,13 @@
 // is masked, so nothing is padded to the largest load.  The grid is sized from an upper bound
 // of the tile count (the host never reads the counts); surplus blocks exit at once.
 //
-// Tiling: BM x BN output tile per block, BK-deep slices staged through LDS (double buffered,
-// next slice prefetched into registers while the current one is multiplied), 32x32x16 bf16 MFMA.
+// Tiling: 256 x 256 output tile per block, 32-deep contraction slices moved from HBM/L2 straight
+// into a 4-deep ring of LDS buffers by buffer loads (no register staging; rows outside a ragged
+// group arrive as zeros because they lie past the end of the buffer resource), 32x32x16 bf16 MFMA.
 // An operand whose contraction index is contiguous in memory is kept row-major in LDS and read
 // with 16-byte loads; one whose contraction index is the slow one is kept as it is and read with
-// the transposing LDS load, so no operand is ever transposed in HBM.  The MFMA is issued with the
+// the transposing LDS load, so no operand is ever transposed in HBM.  Both layouts are
+// XOR-swizzled so that fragment reads are free of bank conflicts.  The MFMA is issued with the
 // operands swapped, which leaves every lane with four consecutive output columns of one row and
 // gives 8/16-byte stores.
 #include "internal.h"
@@ -57,79 +59,31 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
 }
 __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
-template <int BM_, int BN_, int BK_, int WGM_, int WGN_>
-struct Tile {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
-    static constexpr int NT = WGM * WGN * 64;
-    static constexpr int WM = BM / WGM, WN = BN / WGN;
-    static constexpr int TM = WM / 32, TN = WN / 32;
-    static constexpr int PITCH_R = BK + 8;                 // K-contiguous tile: [rows][BK], padded
-    static constexpr int PITCH_CM = BM + 32, PITCH_CN = BN + 32;   // K-major tile: [BK][cols], padded
-    static constexpr int A_R = BM * PITCH_R, A_C = BK * PITCH_CM;
-    static constexpr int B_R = BN * PITCH_R, B_C = BK * PITCH_CN;
-};
+// Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
+// staged through a 4-deep ring of LDS buffers (16 KB per operand per slice).
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4, NT = 512;
+constexpr int WGM = 2, WGN = 4, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
+constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
 
-// ---- global -> registers -> LDS -----------------------------------------------------------------
-// A tile of ROWS x COLS elements, COLS contiguous in memory, moved as 16-byte pieces.
-// Piece q = p * NT + tid sits at row q / (COLS/8), column 8 * (q % (COLS/8)).
-template <int ROWS, int COLS, int NT>
-struct Mover {
-    static constexpr int PIECES = ROWS * COLS / 8;
-    static constexpr int PER = (PIECES + NT - 1) / NT;
-    static constexpr int CPR = COLS / 8;
+// ---- LDS layouts (byte offsets inside one operand buffer) --------------------------------------
+// K-contiguous operand: [256 rows][32 steps], 64 bytes per row, 16-byte pieces XOR-swizzled by the
+// row so that 16 consecutive rows of one piece cover all banks.
+__device__ __forceinline__ uint32_t kcontig_off(int row, int piece) { return row * 64 + ((piece ^ ((row >> 2) & 3)) << 4); }
+// K-major operand: [32 steps][COLS columns]; 64-byte granules of a row XOR-swizzled by the step so
+// that the four steps a transposing load touches fall into different banks.
+template <int COLS>
+__device__ __forceinline__ uint32_t kmajor_off(int krow, int col) { return krow * (COLS * 2) + ((((col >> 5) ^ (krow & 3))) << 6) + (col & 31) * 2; }
 
-    // rows [row0, row0+ROWS) x columns [col0, col0+COLS) of a matrix with leading dimension ld;
-    // rows >= row_end and columns >= col_end read as zero.  With DUAL the right half of the tile
-    // comes from `base2` at the same columns as the left half.
-    template <bool DUAL>
-    static __device__ __forceinline__ void load(uint4 (&r)[PER], const bf16_t* base, const bf16_t* base2, long ld,
-                                                long row0, long row_end, int col0, int col_end, int tid)
-    {
-#pragma unroll
-        for (int p = 0; p < PER; ++p) {
-            const int q = p * NT + tid;
-            const int row = q / CPR;
-            int c = (q % CPR) * 8;
-            const bf16_t* src = base;
-            if (DUAL) {
-                if (c >= COLS / 2) { src = base2; c -= COLS / 2; }
-            }
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if ((PIECES % NT == 0 || q < PIECES) && row0 + row < row_end && col0 + c < col_end)
-                v = *reinterpret_cast<const uint4*>(src + (row0 + row) * ld + col0 + c);
-            r[p] = v;
-        }
-    }
-    template <int PITCH>
-    static __device__ __forceinline__ void store(const uint4 (&r)[PER], bf16_t* tile, int tid)
-    {
-#pragma unroll
-        for (int p = 0; p < PER; ++p) {
-            const int q = p * NT + tid;
-            if (PIECES % NT == 0 || q < PIECES)
-                *reinterpret_cast<uint4*>(tile + (q / CPR) * PITCH + (q % CPR) * 8) = r[p];
-        }
-    }
-};
-
-// ---- LDS -> MFMA operand fragments --------------------------------------------------------------
 // Fragment = 32 rows (or columns) x 16 contraction steps; lane l holds row l%32, steps 8*(l/32)..+7.
-template <int PITCH>
-__device__ __forceinline__ bf16x8 frag_kcontig(const bf16_t* tile, int row_base, int kk, int lane)
+__device__ __forceinline__ bf16x8 lds_frag_kcontig(uint32_t addr) { return *(LDS_PTR(bf16x8))(uintptr_t)addr; }
+// The transposing load works on blocks of 16 lanes: lane s of a block points at 4 consecutive columns
+// of step s/4; lane i of the block receives column i of steps 0..3.  Two loads give the 8 steps of a
+// lane in the same order as the K-contiguous fragment.
+__device__ __forceinline__ bf16x8 lds_frag_kmajor(uint32_t addr, uint32_t row4_bytes)
 {
-    const bf16_t* p = tile + (row_base + (lane & 31)) * PITCH + kk + 8 * (lane >> 5);
-    return *reinterpret_cast<const bf16x8*>(p);
-}
-// Tile stored [contraction step][column].  The transposing load works on blocks of 16 lanes: lane s of
-// a block points at 4 consecutive columns of step (s/4); lane i of the block receives column i of
-// steps 0..3.  Two loads give the 8 steps of a lane in the same order as frag_kcontig.
-template <int PITCH>
-__device__ __forceinline__ bf16x8 frag_kmajor(const bf16_t* tile, int col_base, int kk, int lane)
-{
-    const int b = lane >> 4, s = lane & 15;
-    const bf16_t* p = tile + (kk + 8 * (b >> 1) + (s >> 2)) * PITCH + col_base + 16 * (b & 1) + 4 * (s & 3);
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p + 4 * PITCH));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)addr);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)(addr + row4_bytes));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
 }
@@ -144,23 +98,49 @@ __device__ __forceinline__ void unpack4(uint2 v, float* f)
     f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
 }
 
-// ---- the kernel ---------------------------------------------------------------------------------
-template <class TC, int KIND, int EPI>
-__global__ __launch_bounds__(TC::NT) void grouped_gemm_kernel(const GemmParams p)
+typedef __attribute__((ext_vector_type(4))) int rsrc_t;     // raw buffer resource (4 scalar registers)
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, long long bytes)
 {
-    constexpr int BM = TC::BM, BN = TC::BN, BK = TC::BK, NT = TC::NT;
+    if (bytes < 0) bytes = 0;
+    if (bytes > 0xffffffffll) bytes = 0xffffffffll;
+    const unsigned long long b = (unsigned long long)base;
+    rsrc_t r;
+    r[0] = (int)(unsigned)(b & 0xffffffffull);
+    r[1] = (int)(unsigned)((b >> 32) & 0xffffull);         // stride 0: raw buffer, byte offsets
+    r[2] = (int)(unsigned)bytes;                           // bytes past this limit read as zero
+    r[3] = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from a buffer straight into LDS at lds_base + lane*16 (lds_base is uniform and
+// goes through M0); bytes past the end of the buffer arrive as zeros.  Issued as assembly so that
+// the compiler does not serialise later LDS reads of other ring slots behind it; completion is
+// tracked by hand with WAIT_VMCNT before the barrier that publishes the slot.
+__device__ __forceinline__ void dma16(rsrc_t r, uint32_t lds_base, uint32_t voff, uint32_t soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(r), "s"(soff) : "memory");
+}
+
+#define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+#define BLOCK_BARRIER() asm volatile("s_barrier" ::: "memory")
+
+// ---- the kernel ---------------------------------------------------------------------------------
+template <int KIND, int EPI>
+__global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
+{
     constexpr bool A_KMAJOR = (KIND == KIND_TN);
     constexpr bool B_KMAJOR = (KIND != KIND_NT);
     constexpr bool DUAL = (EPI == EPI_FWD1_SWIGLU);
-    constexpr int A_ELEMS = A_KMAJOR ? TC::A_C : TC::A_R;
-    constexpr int B_ELEMS = B_KMAJOR ? TC::B_C : TC::B_R;
-    constexpr int STAGE = A_ELEMS + B_ELEMS;
-    static_assert(!DUAL || (TC::TN % 2 == 0), "dual-B needs an even number of column fragments per wave");
+    static_assert(!DUAL || (TN % 2 == 0), "dual-B needs an even number of column fragments per wave");
 
-    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_PTR(unsigned char))smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / TC::WGN, wn = wave % TC::WGN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
 
     // ---- which tile: spread consecutive tiles over one XCD (blocks go round-robin over 8 XCDs),
     //      then walk bands of 8 row tiles column by column so that neighbours share operands
@@ -217,92 +197,182 @@ __global__ __launch_bounds__(TC::NT) void grouped_gemm_kernel(const GemmParams p
     const int n0 = ct * (DUAL ? BN / 2 : BN);             // first output column (hidden unit for dual)
     const int k_per_seg = (KIND == KIND_TN) ? k_tiles : p.Kseg / BK;
 
-    using MovA = Mover<A_KMAJOR ? BK : BM, A_KMAJOR ? BM : BK, NT>;
-    using MovB = Mover<B_KMAJOR ? BK : BN, B_KMAJOR ? BN : BK, NT>;
-    uint4 ra[MovA::PER], rb[MovB::PER];
-
-    auto load_slice = [&](int kt) {
-        const int seg = (KIND == KIND_TN) ? 0 : kt / k_per_seg;
-        const int k0 = (kt - seg * k_per_seg) * BK;
-        const bf16_t* Ab = p.A[seg];
-        const bf16_t* Bb = p.B[seg] + (long)g * p.b_group_stride;
+    // ---- buffer resources: everything outside the valid rows of an operand reads as zero --------
+    // Each wave moves two 1-KB pieces of the A slice and two of the B slice per contraction slice.
+    rsrc_t rA[2], rB[2];                   // per segment (A), per segment or per dual half (B)
+    uint32_t voffA[2], voffB[2];                           // per-lane byte offsets of this wave's two pieces
+    uint32_t ldsA[2], ldsB[2];                             // LDS byte offsets of the pieces inside a stage
+    uint32_t stepA, stepB;                                 // byte advance of the source per slice
+    {
+        const long a_rows = a_row_end - a_row0;
         if (KIND == KIND_TN) {
-            // A tile: contraction rows [a_row0 + k0, +BK) x output rows [m0, m0+BM) of a [rows, Mout] matrix
-            MovA::template load<false>(ra, Ab, Ab, p.lda, a_row0 + k0, a_row_end, m0, p.Mout, tid);
-            MovB::template load<false>(rb, Bb, Bb, p.ldb, a_row0 + k0, a_row_end, n0, p.N, tid);
+            rA[0] = rA[1] = make_rsrc(p.A[0] + a_row0 * p.lda + m0, (a_rows * p.lda - m0) * 2);
+            rB[0] = rB[1] = make_rsrc(p.B[0] + a_row0 * p.ldb + n0, (a_rows * p.ldb - n0) * 2);
+            stepA = (uint32_t)(BK * p.lda * 2);
+            stepB = (uint32_t)(BK * p.ldb * 2);
         } else {
-            MovA::template load<false>(ra, Ab, Ab, p.lda, a_row0, a_row_end, k0, p.Kseg, tid);
+            for (int s = 0; s < 2; ++s) {
+                const int ss = s < p.n_seg ? s : 0;
+                rA[s] = make_rsrc(p.A[ss] + a_row0 * p.lda, a_rows * p.lda * 2);
+            }
+            stepA = BK * 2;
+            const long gofs = (long)g * p.b_group_stride;
             if (KIND == KIND_NN) {
-                const bf16_t* B2 = DUAL ? p.B_dual + (long)g * p.b_group_stride : Bb;
-                MovB::template load<DUAL>(rb, Bb, B2, p.ldb, k0, p.Kseg, n0, p.N, tid);
+                rB[0] = make_rsrc(p.B[0] + gofs + n0, ((long)p.Kseg * p.ldb - n0) * 2);
+                rB[1] = DUAL ? make_rsrc(p.B_dual + gofs + n0, ((long)p.Kseg * p.ldb - n0) * 2) : rB[0];
+                stepB = (uint32_t)(BK * p.ldb * 2);
             } else {
-                MovB::template load<false>(rb, Bb, Bb, p.ldb, n0, p.N, k0, p.Kseg, tid);
+                for (int s = 0; s < 2; ++s) {
+                    const int ss = s < p.n_seg ? s : 0;
+                    rB[s] = make_rsrc(p.B[ss] + gofs + (long)n0 * p.ldb, (long)(p.N - n0) * p.ldb * 2);
+                }
+                stepB = BK * 2;
             }
         }
-    };
-    auto store_slice = [&](int stage) {
-        bf16_t* sa = smem + stage * STAGE;
-        bf16_t* sb = sa + A_ELEMS;
-        if (A_KMAJOR) MovA::template store<TC::PITCH_CM>(ra, sa, tid); else MovA::template store<TC::PITCH_R>(ra, sa, tid);
-        if (B_KMAJOR) MovB::template store<TC::PITCH_CN>(rb, sb, tid); else MovB::template store<TC::PITCH_R>(rb, sb, tid);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int blk = wave + 8 * i;                  // piece index inside a 16-KB operand buffer
+            const int L = blk * 64 + lane;                 // 16-byte slot inside the buffer
+            ldsA[i] = blk * 1024;
+            if (A_KMAJOR) {
+                const int krow = L >> 5, pp = L & 31, col = (((pp >> 2) ^ (krow & 3)) << 5) + (pp & 3) * 8;
+                voffA[i] = (uint32_t)((krow * p.lda + col) * 2);
+            } else {
+                const int row = L >> 2, piece = (L & 3) ^ ((row >> 2) & 3);
+                voffA[i] = (uint32_t)((row * p.lda + piece * 8) * 2);
+            }
+            if (!B_KMAJOR) {
+                ldsB[i] = blk * 1024;
+                const int row = L >> 2, piece = (L & 3) ^ ((row >> 2) & 3);
+                voffB[i] = (uint32_t)((row * p.ldb + piece * 8) * 2);
+            } else if (DUAL) {
+                // two sub-buffers of [32][128]; piece i of this wave belongs to half i
+                const int L2 = wave * 64 + lane;
+                ldsB[i] = i * 8192 + wave * 1024;
+                const int krow = L2 >> 4, pp = L2 & 15, col = (((pp >> 2) ^ (krow & 3)) << 5) + (pp & 3) * 8;
+                voffB[i] = (uint32_t)((krow * p.ldb + col) * 2);
+            } else {
+                ldsB[i] = blk * 1024;
+                const int krow = L >> 5, pp = L & 31, col = (((pp >> 2) ^ (krow & 3)) << 5) + (pp & 3) * 8;
+                voffB[i] = (uint32_t)((krow * p.ldb + col) * 2);
+            }
+        }
+    }
+
+    // Slices are requested strictly in order; the source offsets advance with the stream.
+    int iss_t = 0, iss_in_seg = 0, iss_seg = 0;
+    uint32_t soffA = 0, soffB = 0;
+    auto issue_next = [&]() {                              // slice iss_t -> stage iss_t % STAGES
+        const uint32_t st = lds0 + (uint32_t)(iss_t & (STAGES - 1)) * STAGE_BYTES;
+        const rsrc_t ra = iss_seg ? rA[1] : rA[0];
+        dma16(ra, st + ldsA[0], voffA[0], soffA);
+        dma16(ra, st + ldsA[1], voffA[1], soffA);
+        if (DUAL) {
+            dma16(rB[0], st + OPER_BYTES + ldsB[0], voffB[0], soffB);
+            dma16(rB[1], st + OPER_BYTES + ldsB[1], voffB[1], soffB);
+        } else {
+            const rsrc_t rb = (KIND == KIND_NT && iss_seg) ? rB[1] : rB[0];
+            dma16(rb, st + OPER_BYTES + ldsB[0], voffB[0], soffB);
+            dma16(rb, st + OPER_BYTES + ldsB[1], voffB[1], soffB);
+        }
+        ++iss_t; ++iss_in_seg;
+        soffA += stepA; soffB += stepB;
+        if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
     };
 
-    f32x16 acc[TC::TM][TC::TN];
+    // ---- per-lane fragment addresses inside a stage (step half 0; half 1 is a fixed distance away)
+    uint32_t fa_addr[TM], fb_addr[TN];
+    constexpr uint32_t A_HALF = A_KMAJOR ? 16 * (BM * 2) : 0;      // K-major: 16 steps further down
+    constexpr int BCOLS = DUAL ? BN / 2 : BN;
+    constexpr uint32_t B_HALF = B_KMAJOR ? 16 * (BCOLS * 2) : 0;
 #pragma unroll
-    for (int i = 0; i < TC::TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        const int r = wm * WM + i * 32;
+        if (A_KMAJOR) {
+            const int b = lane >> 4, s = lane & 15;
+            fa_addr[i] = kmajor_off<BM>(8 * (b >> 1) + (s >> 2), r + 16 * (b & 1) + 4 * (s & 3));
+        } else {
+            fa_addr[i] = kcontig_off(r + (lane & 31), lane >> 5);
+        }
+    }
 #pragma unroll
-        for (int j = 0; j < TC::TN; ++j)
+    for (int j = 0; j < TN; ++j) {
+        if (!B_KMAJOR) {
+            fb_addr[j] = OPER_BYTES + kcontig_off(wn * WN + j * 32 + (lane & 31), lane >> 5);
+        } else {
+            const int b = lane >> 4, s = lane & 15;
+            const int krow = 8 * (b >> 1) + (s >> 2), cofs = 16 * (b & 1) + 4 * (s & 3);
+            if (DUAL)   // even fragments from the W1 sub-buffer, odd ones from the W3 sub-buffer
+                fb_addr[j] = OPER_BYTES + (j & 1) * 8192 + kmajor_off<BN / 2>(krow, wn * (WN / 2) + (j >> 1) * 32 + cofs);
+            else
+                fb_addr[j] = OPER_BYTES + kmajor_off<BN>(krow, wn * WN + j * 32 + cofs);
+        }
+    }
+    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int t, int half) {
+        const uint32_t st = lds0 + (uint32_t)(t & (STAGES - 1)) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[i] = A_KMAJOR ? lds_frag_kmajor(st + fa_addr[i] + half * A_HALF, 4 * BM * 2)
+                             : lds_frag_kcontig(st + (fa_addr[i] ^ (half ? 32u : 0u)));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[j] = B_KMAJOR ? lds_frag_kmajor(st + fb_addr[j] + half * B_HALF, 4 * BCOLS * 2)
+                             : lds_frag_kcontig(st + (fb_addr[j] ^ (half ? 32u : 0u)));
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    };
+
+    // ---- main loop.  Invariant: the barrier that ends iteration t-1 makes slice t+1 visible to
+    // every wave, so the first fragments of slice t+1 are fetched before the barrier of iteration t
+    // and the matrix pipe never drains.  Slice t+3 is requested at the top of iteration t and must
+    // have landed when iteration t+1 ends: two iterations of latency cover.
     if (k_tiles > 0) {
-        load_slice(0);
-        store_slice(0);
-    }
-    __syncthreads();
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < k_tiles;
-        if (more) load_slice(kt + 1);
-        const bf16_t* sa = smem + cur * STAGE;
-        const bf16_t* sb = sa + A_ELEMS;
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 fa[TC::TM], fb[TC::TN];
-#pragma unroll
-            for (int i = 0; i < TC::TM; ++i) {
-                const int r = wm * TC::WM + i * 32;
-                fa[i] = A_KMAJOR ? frag_kmajor<TC::PITCH_CM>(sa, r, kk, lane) : frag_kcontig<TC::PITCH_R>(sa, r, kk, lane);
-            }
-#pragma unroll
-            for (int j = 0; j < TC::TN; ++j) {
-                // dual: even fragments come from the left half (W1), odd ones from the right half (W3)
-                const int c = DUAL ? (j & 1) * (BN / 2) + wn * (TC::WN / 2) + (j >> 1) * 32 : wn * TC::WN + j * 32;
-                fb[j] = B_KMAJOR ? frag_kmajor<TC::PITCH_CN>(sb, c, kk, lane) : frag_kcontig<TC::PITCH_R>(sb, c, kk, lane);
-            }
-#pragma unroll
-            for (int i = 0; i < TC::TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TC::TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+        issue_next();
+        if (k_tiles > 1) issue_next();
+        if (k_tiles > 2) issue_next();
+        if (k_tiles > 2) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+        BLOCK_BARRIER();
+        load_frags(fa0, fb0, 0, 0);
+        for (int t = 0; t < k_tiles; ++t) {
+            const bool more3 = t + 3 < k_tiles;
+            if (more3) issue_next();
+            load_frags(fa1, fb1, t, 1);
+            mma(fa0, fb0);
+            if (t + 1 < k_tiles) load_frags(fa0, fb0, t + 1, 0);
+            mma(fa1, fb1);
+            if (more3) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+            BLOCK_BARRIER();
         }
-        if (more) store_slice(cur ^ 1);
-        __syncthreads();
     }
 
     // ---- epilogue: lane holds row (l%32) of each fragment and columns q*8 + (l/32)*4 + 0..3
     const int lrow = lane & 31, lcol = (lane >> 5) * 4;
     const long row_limit = (KIND == KIND_TN) ? (long)p.Mout : a_row_end;
 #pragma unroll
-    for (int i = 0; i < TC::TM; ++i) {
-        const long row = (long)m0 + wm * TC::WM + i * 32 + lrow;
+    for (int i = 0; i < TM; ++i) {
+        const long row = (long)m0 + wm * WM + i * 32 + lrow;
         if (row >= row_limit) continue;
         if (EPI == EPI_FWD1_SWIGLU) {
 #pragma unroll
-            for (int j = 0; j < TC::TN; j += 2) {
+            for (int j = 0; j < TN; j += 2) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * (TC::WN / 2) + (j >> 1) * 32 + q * 8 + lcol;
+                    const int col = n0 + wn * (WN / 2) + (j >> 1) * 32 + q * 8 + lcol;
                     if (col >= p.N) continue;
                     float z[4], u[4], a[4];
 #pragma unroll
@@ -319,10 +389,10 @@ __global__ __launch_bounds__(TC::NT) void grouped_gemm_kernel(const GemmParams p
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < TC::TN; ++j) {
+            for (int j = 0; j < TN; ++j) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * TC::WN + j * 32 + q * 8 + lcol;
+                    const int col = n0 + wn * WN + j * 32 + q * 8 + lcol;
                     if (col >= p.N) continue;
                     float v[4];
 #pragma unroll
@@ -363,35 +433,29 @@ __global__ __launch_bounds__(TC::NT) void grouped_gemm_kernel(const GemmParams p
 }
 
 // ---- host side ----------------------------------------------------------------------------------
-using TileMain = Tile<256, 256, 64, 2, 4>;     // 8 waves, 128 x 64 per wave
-
-template <class TC, int KIND, int EPI>
+template <int KIND, int EPI>
 hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st)
 {
-    constexpr bool A_KMAJOR = (KIND == KIND_TN);
-    constexpr bool B_KMAJOR = (KIND != KIND_NT);
     constexpr bool DUAL = (EPI == EPI_FWD1_SWIGLU);
-    constexpr int STAGE = (A_KMAJOR ? TC::A_C : TC::A_R) + (B_KMAJOR ? TC::B_C : TC::B_R);
-    constexpr size_t LDS = (size_t)2 * STAGE * sizeof(bf16_t);
-    const int bn = DUAL ? TC::BN / 2 : TC::BN;
+    const int bn = DUAL ? BN / 2 : BN;
     p.col_tiles = (p.N + bn - 1) / bn;
     if (KIND == KIND_TN) {
-        p.row_tiles = (p.Mout + TC::BM - 1) / TC::BM;
+        p.row_tiles = (p.Mout + BM - 1) / BM;
         p.n_tiles = n_groups_cap * p.row_tiles * p.col_tiles;
     } else {
-        p.row_tiles = (rows_upper + TC::BM - 1) / TC::BM + n_groups_cap;
+        p.row_tiles = (rows_upper + BM - 1) / BM + n_groups_cap;
         p.n_tiles = p.row_tiles * p.col_tiles;
     }
     if (p.n_tiles == 0) return hipSuccess;
     const int grid = (p.n_tiles + 7) / 8 * 8;
-    auto kern = grouped_gemm_kernel<TC, KIND, EPI>;
+    auto kern = grouped_gemm_kernel<KIND, EPI>;
     static bool configured = false;      // per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(TC::NT), LDS, st, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), LDS_BYTES, st, p);
     return hipGetLastError();
 }
 
@@ -417,8 +481,8 @@ hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         p.A[0] = (const bf16_t*)a.Xp; p.B[0] = (const bf16_t*)a.W1; p.B_dual = (const bf16_t*)a.W3;
         p.lda = d; p.ldb = h; p.b_group_stride = d * h; p.Kseg = s.d; p.N = s.h;
         p.O0 = (bf16_t*)a.Z; p.O1 = (bf16_t*)a.U; p.O2 = (bf16_t*)a.Act; p.ldo = h;
-        e = (s.act == MOE_ACT_SWIGLU) ? launch<TileMain, KIND_NN, EPI_FWD1_SWIGLU>(p, A, s.G, st)
-                                      : launch<TileMain, KIND_NN, EPI_FWD1_GELU>(p, A, s.G, st);
+        e = (s.act == MOE_ACT_SWIGLU) ? launch<KIND_NN, EPI_FWD1_SWIGLU>(p, A, s.G, st)
+                                      : launch<KIND_NN, EPI_FWD1_GELU>(p, A, s.G, st);
         if (e != hipSuccess) return e;
     }
     {   // fwd2: Act [rows, h] x W2[g] (h x d)
@@ -426,7 +490,7 @@ hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         p.A[0] = (const bf16_t*)a.Act; p.B[0] = (const bf16_t*)a.W2;
         p.lda = h; p.ldb = d; p.b_group_stride = d * h; p.Kseg = s.h; p.N = s.d;
         p.O0 = (bf16_t*)a.Yp; p.ldo = d;
-        e = launch<TileMain, KIND_NN, EPI_BF16>(p, A, s.G, st);
+        e = launch<KIND_NN, EPI_BF16>(p, A, s.G, st);
     }
     return e;
 }
@@ -444,8 +508,8 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
             p.lda = d; p.ldb = d; p.b_group_stride = d * h; p.Kseg = s.d; p.N = s.h;
             p.O0 = (bf16_t*)a.dZ; p.O1 = (bf16_t*)a.dU; p.O2 = (bf16_t*)a.Act; p.ldo = h;
             p.Zin = (const bf16_t*)a.Z; p.Uin = (const bf16_t*)a.U;
-            e = swiglu ? launch<TileMain, KIND_NT, EPI_BWD1_SWIGLU>(p, A, s.G, st)
-                       : launch<TileMain, KIND_NT, EPI_BWD1_GELU>(p, A, s.G, st);
+            e = swiglu ? launch<KIND_NT, EPI_BWD1_SWIGLU>(p, A, s.G, st)
+                       : launch<KIND_NT, EPI_BWD1_GELU>(p, A, s.G, st);
             if (e != hipSuccess) return e;
         }
         {   // bwd2: dXp = dZ [rows, h] x W1[g]^T (+ dU x W3[g]^T)
@@ -455,7 +519,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
             p.n_seg = swiglu ? 2 : 1;
             p.lda = h; p.ldb = h; p.b_group_stride = d * h; p.Kseg = s.h; p.N = s.d;
             p.O0 = (bf16_t*)a.dXp; p.ldo = d;
-            e = launch<TileMain, KIND_NT, EPI_BF16>(p, A, s.G, st);
+            e = launch<KIND_NT, EPI_BF16>(p, A, s.G, st);
             if (e != hipSuccess) return e;
         }
     }
@@ -465,7 +529,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         p.A[0] = (const bf16_t*)L; p.B[0] = (const bf16_t*)R;
         p.lda = ldl; p.ldb = ldr; p.b_group_stride = 0; p.Mout = Mout; p.N = N;
         p.OF = out; p.ldo = N; p.o_group_stride = d * h;
-        return launch<TileMain, KIND_TN, EPI_F32>(p, A, s.G, st);
+        return launch<KIND_TN, EPI_F32>(p, A, s.G, st);
     };
     e = wgrad(a.Xp, d, s.d, a.dZ, h, s.h, a.dW1);
     if (e != hipSuccess) return e;
