@@ -28,7 +28,7 @@ FLAGS = [
 def _compile(unit: str) -> str:
     src = os.path.join(CSRC, unit + ".hip")
     obj = os.path.join(OBJ, unit + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+    cmd = [HIPCC, *FLAGS, *os.environ.get("MOE_EXTRA_FLAGS", "").split(), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -142,53 +142,56 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- which tile: spread consecutive tiles over one XCD (blocks go round-robin over 8 XCDs),
-    //      then walk bands of 8 row tiles column by column so that neighbours share operands
-    int tile_id;
-    {
-        const int nb = gridDim.x, per = nb >> 3;           // nb is a multiple of 8
-        tile_id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    }
-    if (tile_id >= p.n_tiles) return;
+    // ---- which tile.  Blocks go round-robin over the 8 XCDs (block b runs on XCD b % 8), each with
+    // its own L2, so XCD x takes a contiguous, equally sized share of the tiles that actually exist
+    // (the grid is an upper bound; the counts are only known here), and walks it in bands of 8 row
+    // tiles, column by column, so that the 32 tiles in flight on an XCD share operand slices.
     int first_slot, n_groups;
     hosted_range(p.dest_slots, p.self, p.Gcap, first_slot, n_groups);
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
 
     int g, rt, ct;
-    {
-        int rem = tile_id, row_tiles = p.row_tiles;
-        g = 0;
-        if (KIND == KIND_TN) {
-            const int per_group = p.row_tiles * p.col_tiles;
-            g = rem / per_group;
-            rem -= g * per_group;
-        }
-        const int band = rem / (8 * p.col_tiles);
-        const int in_band = rem - band * 8 * p.col_tiles;
-        const int band_rows = min(8, row_tiles - band * 8);
-        rt = band * 8 + in_band % band_rows;
-        ct = in_band / band_rows;
-    }
-
     long a_row0, a_row_end;      // valid rows of the A tile (NN/NT) or of the contraction (TN)
     int k_tiles;
     int m0;                      // first output row of the tile (global row for NN/NT, row of dW for TN)
     if (KIND == KIND_TN) {
+        // every group has the same tile grid but its own contraction length: each XCD takes an
+        // eighth of every group's tiles, so the work per XCD is balanced whatever the group sizes
+        const int tiles_g = p.row_tiles * p.col_tiles;
+        const int cg = (tiles_g + 7) >> 3;
+        g = q / cg;
+        const int t = xcd * cg + (q - g * cg);
+        if (g >= p.Gcap || t >= tiles_g) return;
+        const int band = t / (8 * p.col_tiles);
+        const int in_band = t - band * 8 * p.col_tiles;
+        const int band_rows = min(8, p.row_tiles - band * 8);
+        rt = band * 8 + in_band % band_rows;
+        ct = in_band / band_rows;
         int row0 = 0, rows = 0;
         if (g < n_groups) { row0 = p.slot_offsets[first_slot + g]; rows = p.slot_offsets[first_slot + g + 1] - row0; }
         a_row0 = row0; a_row_end = row0 + rows;
         k_tiles = (rows + BK - 1) / BK;
         m0 = rt * BM;
     } else {
-        int acc = 0;
-        bool found = false;
-        int gg = 0, row0 = 0, row_end = 0;
+        int total_rt = 0;
+        for (int gg = 0; gg < n_groups; ++gg)
+            total_rt += (p.slot_offsets[first_slot + gg + 1] - p.slot_offsets[first_slot + gg] + BM - 1) / BM;
+        const int n_act = total_rt * p.col_tiles;
+        const int per = (n_act + 7) >> 3;
+        const int t = xcd * per + q;
+        if (q >= per || t >= n_act) return;
+        const int band = t / (8 * p.col_tiles);
+        const int in_band = t - band * 8 * p.col_tiles;
+        const int band_rows = min(8, total_rt - band * 8);
+        rt = band * 8 + in_band % band_rows;
+        ct = in_band / band_rows;
+        int acc = 0, gg = 0, row0 = 0, row_end = 0;
         for (; gg < n_groups; ++gg) {
             const int o = p.slot_offsets[first_slot + gg], e = p.slot_offsets[first_slot + gg + 1];
             const int nt = (e - o + BM - 1) / BM;
-            if (rt < acc + nt) { row0 = o + (rt - acc) * BM; row_end = e; found = true; break; }
+            if (rt < acc + nt) { row0 = o + (rt - acc) * BM; row_end = e; break; }
             acc += nt;
         }
-        if (!found) return;
         g = gg;
         a_row0 = row0; a_row_end = row_end;
         k_tiles = p.n_seg * (p.Kseg / BK);
@@ -265,8 +268,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     auto issue_next = [&]() {                              // slice iss_t -> stage iss_t % STAGES
         const uint32_t st = lds0 + (uint32_t)(iss_t & (STAGES - 1)) * STAGE_BYTES;
         const rsrc_t ra = iss_seg ? rA[1] : rA[0];
+#ifndef EXP_NO_A
         dma16(ra, st + ldsA[0], voffA[0], soffA);
         dma16(ra, st + ldsA[1], voffA[1], soffA);
+#endif
+#ifndef EXP_NO_B
         if (DUAL) {
             dma16(rB[0], st + OPER_BYTES + ldsB[0], voffB[0], soffB);
             dma16(rB[1], st + OPER_BYTES + ldsB[1], voffB[1], soffB);
@@ -275,6 +281,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             dma16(rb, st + OPER_BYTES + ldsB[0], voffB[0], soffB);
             dma16(rb, st + OPER_BYTES + ldsB[1], voffB[1], soffB);
         }
+#endif
         ++iss_t; ++iss_in_seg;
         soffA += stepA; soffB += stepB;
         if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
@@ -350,12 +357,26 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         load_frags(fa0, fb0, 0, 0);
         for (int t = 0; t < k_tiles; ++t) {
             const bool more3 = t + 3 < k_tiles;
+#ifndef EXP_NO_DMA
             if (more3) issue_next();
+#endif
+#ifndef EXP_NO_LDS
             load_frags(fa1, fb1, t, 1);
+#endif
+#ifndef EXP_NO_MMA
             mma(fa0, fb0);
+#endif
+#ifndef EXP_NO_LDS
             if (t + 1 < k_tiles) load_frags(fa0, fb0, t + 1, 0);
+#endif
+#ifndef EXP_NO_MMA
             mma(fa1, fb1);
+#endif
+#ifdef EXP_VM8
+            if (more3) WAIT_VMCNT(8); else WAIT_VMCNT(0);
+#else
             if (more3) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+#endif
             BLOCK_BARRIER();
         }
     }
@@ -439,15 +460,17 @@ hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st
     constexpr bool DUAL = (EPI == EPI_FWD1_SWIGLU);
     const int bn = DUAL ? BN / 2 : BN;
     p.col_tiles = (p.N + bn - 1) / bn;
+    int grid;
     if (KIND == KIND_TN) {
         p.row_tiles = (p.Mout + BM - 1) / BM;
         p.n_tiles = n_groups_cap * p.row_tiles * p.col_tiles;
+        grid = 8 * n_groups_cap * ((p.row_tiles * p.col_tiles + 7) / 8);
     } else {
-        p.row_tiles = (rows_upper + BM - 1) / BM + n_groups_cap;
+        p.row_tiles = (rows_upper + BM - 1) / BM + n_groups_cap;      // upper bound of the row tiles
         p.n_tiles = p.row_tiles * p.col_tiles;
+        grid = (p.n_tiles + 7) / 8 * 8;
     }
     if (p.n_tiles == 0) return hipSuccess;
-    const int grid = (p.n_tiles + 7) / 8 * 8;
     auto kern = grouped_gemm_kernel<KIND, EPI>;
     static bool configured = false;      // per instantiation
     if (!configured) {
