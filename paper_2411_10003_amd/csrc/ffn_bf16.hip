@@ -64,7 +64,10 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4, NT = 512;
 constexpr int WGM = 2, WGN = 4, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
 constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
-constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
+constexpr int EP_PITCH = 64 * 4 + 16;       // epilogue patch: bytes per staged row of 64 floats (padded against bank conflicts)
+constexpr int EP_WAVE = 64 * EP_PITCH;      // 64 rows per wave at a time
+constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_BYTES;
+constexpr size_t LDS_BYTES = RING_BYTES > (size_t)8 * EP_WAVE ? RING_BYTES : (size_t)8 * EP_WAVE;
 
 // ---- LDS layouts (byte offsets inside one operand buffer) --------------------------------------
 // K-contiguous operand: [256 rows][32 steps], 64 bytes per row, 16-byte pieces XOR-swizzled by the
@@ -86,16 +89,6 @@ __device__ __forceinline__ bf16x8 lds_frag_kmajor(uint32_t addr, uint32_t row4_b
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)(addr + row4_bytes));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, v);
-}
-
-__device__ __forceinline__ uint2 pack4(float a, float b, float c, float d)
-{
-    return make_uint2(pack_bf16x2(a, b), pack_bf16x2(c, d));
-}
-__device__ __forceinline__ void unpack4(uint2 v, float* f)
-{
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
 }
 
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;     // raw buffer resource (4 scalar registers)
@@ -381,73 +374,101 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         }
     }
 
-    // ---- epilogue: lane holds row (l%32) of each fragment and columns q*8 + (l/32)*4 + 0..3
+    // ---- epilogue.  A lane holds, per fragment, row l%32 and columns q*8 + (l/32)*4 + 0..3: storing
+    // from there would touch 16-byte pieces of 32 different rows per instruction.  Instead every wave
+    // passes its 128 x 64 accumulators through its own LDS patch (64 rows at a time, fp32) and reads
+    // them back row-major, 8 consecutive columns per lane, so that global loads and stores move whole
+    // 128/256-byte row segments.  The ring is free: the last barrier of the loop has been passed and
+    // every DMA has landed.
+    unsigned char* patch = smem + wave * EP_WAVE;
     const int lrow = lane & 31, lcol = (lane >> 5) * 4;
     const long row_limit = (KIND == KIND_TN) ? (long)p.Mout : a_row_end;
+    constexpr int CG = DUAL ? 4 : 8;                       // 8-column groups per staged row that carry outputs
+    const int erow = lane / CG, ecg = lane % CG;
+    constexpr int ROWS_PER_PASS = 64 / CG;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const long row = (long)m0 + wm * WM + i * 32 + lrow;
-        if (row >= row_limit) continue;
-        if (EPI == EPI_FWD1_SWIGLU) {
+    for (int half = 0; half < TM / 2; ++half) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int j = 0; j < TN; j += 2) {
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * (WN / 2) + (j >> 1) * 32 + q * 8 + lcol;
-                    if (col >= p.N) continue;
-                    float z[4], u[4], a[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        z[e] = acc[i][j][q * 4 + e];
-                        u[e] = acc[i][j + 1][q * 4 + e];
-                        a[e] = z[e] * sigmoid_f(z[e]) * u[e];
-                    }
-                    const long o = row * p.ldo + col;
-                    *reinterpret_cast<uint2*>(p.O0 + o) = pack4(z[0], z[1], z[2], z[3]);
-                    *reinterpret_cast<uint2*>(p.O1 + o) = pack4(u[0], u[1], u[2], u[3]);
-                    *reinterpret_cast<uint2*>(p.O2 + o) = pack4(a[0], a[1], a[2], a[3]);
+                    const f32x16& a = acc[half * 2 + ii][j];
+                    *reinterpret_cast<float4*>(patch + (ii * 32 + lrow) * EP_PITCH + (j * 32 + q * 8 + lcol) * 4) =
+                        make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
                 }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int pass = 0; pass < 64 / ROWS_PER_PASS; ++pass) {
+            const int r = pass * ROWS_PER_PASS + erow;                     // row inside the 64-row patch
+            const long row = (long)m0 + wm * WM + half * 64 + r;
+            const int col = n0 + (DUAL ? wn * (WN / 2) : wn * WN) + ecg * 8;
+            if (row >= row_limit || col >= p.N) continue;
+            float v[8], u[8];
+            {
+                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + ecg * 32);
+                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + ecg * 32 + 16);
+                v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
             }
-        } else {
+            if (DUAL) {                                                    // columns 32.. of the patch hold x W3
+                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + 128 + ecg * 32);
+                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + 128 + ecg * 32 + 16);
+                u[0] = x0.x; u[1] = x0.y; u[2] = x0.z; u[3] = x0.w; u[4] = x1.x; u[5] = x1.y; u[6] = x1.z; u[7] = x1.w;
+            }
+            const long o = row * p.ldo + col;
+            auto pack8 = [](const float* f) {
+                return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+            };
+            auto unpack8 = [](const uint4 w, float* f) {
+                f[0] = __uint_as_float(w.x << 16); f[1] = __uint_as_float(w.x & 0xffff0000u);
+                f[2] = __uint_as_float(w.y << 16); f[3] = __uint_as_float(w.y & 0xffff0000u);
+                f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
+                f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
+            };
+            if (EPI == EPI_BF16) {
+                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+            } else if (EPI == EPI_F32) {
+                float* dst = p.OF + (long)g * p.o_group_stride + o;
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            } else if (EPI == EPI_FWD1_GELU) {
+                float a[8];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
+                for (int e = 0; e < 8; ++e) a[e] = gelu_f(v[e]);
+                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+            } else if (EPI == EPI_FWD1_SWIGLU) {
+                float a[8];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * WN + j * 32 + q * 8 + lcol;
-                    if (col >= p.N) continue;
-                    float v[4];
+                for (int e = 0; e < 8; ++e) a[e] = v[e] * sigmoid_f(v[e]) * u[e];
+                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+                *reinterpret_cast<uint4*>(p.O1 + o) = pack8(u);
+                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+            } else if (EPI == EPI_BWD1_GELU) {
+                float z[8], dz[8], a[8];
+                unpack8(*reinterpret_cast<const uint4*>(p.Zin + o), z);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][q * 4 + e];
-                    const long o = row * p.ldo + col;
-                    if (EPI == EPI_BF16) {
-                        *reinterpret_cast<uint2*>(p.O0 + o) = pack4(v[0], v[1], v[2], v[3]);
-                    } else if (EPI == EPI_F32) {
-                        *reinterpret_cast<float4*>(p.OF + (long)g * p.o_group_stride + o) = make_float4(v[0], v[1], v[2], v[3]);
-                    } else if (EPI == EPI_FWD1_GELU) {
-                        *reinterpret_cast<uint2*>(p.O0 + o) = pack4(v[0], v[1], v[2], v[3]);
-                        *reinterpret_cast<uint2*>(p.O2 + o) = pack4(gelu_f(v[0]), gelu_f(v[1]), gelu_f(v[2]), gelu_f(v[3]));
-                    } else if (EPI == EPI_BWD1_GELU) {
-                        float z[4];
-                        unpack4(*reinterpret_cast<const uint2*>(p.Zin + o), z);
-                        *reinterpret_cast<uint2*>(p.O0 + o) = pack4(v[0] * gelu_grad_f(z[0]), v[1] * gelu_grad_f(z[1]),
-                                                                   v[2] * gelu_grad_f(z[2]), v[3] * gelu_grad_f(z[3]));
-                        *reinterpret_cast<uint2*>(p.O2 + o) = pack4(gelu_f(z[0]), gelu_f(z[1]), gelu_f(z[2]), gelu_f(z[3]));
-                    } else if (EPI == EPI_BWD1_SWIGLU) {
-                        float z[4], u[4], dz[4], du[4], a[4];
-                        unpack4(*reinterpret_cast<const uint2*>(p.Zin + o), z);
-                        unpack4(*reinterpret_cast<const uint2*>(p.Uin + o), u);
+                for (int e = 0; e < 8; ++e) { dz[e] = v[e] * gelu_grad_f(z[e]); a[e] = gelu_f(z[e]); }
+                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
+                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+            } else if (EPI == EPI_BWD1_SWIGLU) {
+                float z[8], uu[8], dz[8], du[8], a[8];
+                unpack8(*reinterpret_cast<const uint4*>(p.Zin + o), z);
+                unpack8(*reinterpret_cast<const uint4*>(p.Uin + o), uu);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float s = sigmoid_f(z[e]);
-                            du[e] = v[e] * z[e] * s;
-                            dz[e] = v[e] * u[e] * s * (1.0f + z[e] * (1.0f - s));
-                            a[e] = z[e] * s * u[e];
-                        }
-                        *reinterpret_cast<uint2*>(p.O0 + o) = pack4(dz[0], dz[1], dz[2], dz[3]);
-                        *reinterpret_cast<uint2*>(p.O1 + o) = pack4(du[0], du[1], du[2], du[3]);
-                        *reinterpret_cast<uint2*>(p.O2 + o) = pack4(a[0], a[1], a[2], a[3]);
-                    }
+                for (int e = 0; e < 8; ++e) {
+                    const float sg = sigmoid_f(z[e]);
+                    du[e] = v[e] * z[e] * sg;
+                    dz[e] = v[e] * uu[e] * sg * (1.0f + z[e] * (1.0f - sg));
+                    a[e] = z[e] * sg * uu[e];
                 }
+                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
+                *reinterpret_cast<uint4*>(p.O1 + o) = pack8(du);
+                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             }
         }
     }
