@@ -62,6 +62,9 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 4-deep ring of LDS buffers (16 KB per operand per slice).
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4, NT = 512;
+#ifndef BAND
+#define BAND 8
+#endif
 constexpr int WGM = 2, WGN = 4, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
 constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
 constexpr int EP_PITCH = 64 * 4 + 16;       // epilogue patch: bytes per staged row of 64 floats (padded against bank conflicts)
@@ -155,10 +158,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         g = q / cg;
         const int t = xcd * cg + (q - g * cg);
         if (g >= p.Gcap || t >= tiles_g) return;
-        const int band = t / (8 * p.col_tiles);
-        const int in_band = t - band * 8 * p.col_tiles;
-        const int band_rows = min(8, p.row_tiles - band * 8);
-        rt = band * 8 + in_band % band_rows;
+        const int band = t / (BAND * p.col_tiles);
+        const int in_band = t - band * BAND * p.col_tiles;
+        const int band_rows = min(BAND, p.row_tiles - band * BAND);
+        rt = band * BAND + in_band % band_rows;
         ct = in_band / band_rows;
         int row0 = 0, rows = 0;
         if (g < n_groups) { row0 = p.slot_offsets[first_slot + g]; rows = p.slot_offsets[first_slot + g + 1] - row0; }
@@ -173,10 +176,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         const int per = (n_act + 7) >> 3;
         const int t = xcd * per + q;
         if (q >= per || t >= n_act) return;
-        const int band = t / (8 * p.col_tiles);
-        const int in_band = t - band * 8 * p.col_tiles;
-        const int band_rows = min(8, total_rt - band * 8);
-        rt = band * 8 + in_band % band_rows;
+        const int band = t / (BAND * p.col_tiles);
+        const int in_band = t - band * BAND * p.col_tiles;
+        const int band_rows = min(BAND, total_rt - band * BAND);
+        rt = band * BAND + in_band % band_rows;
         ct = in_band / band_rows;
         int acc = 0, gg = 0, row0 = 0, row_end = 0;
         for (; gg < n_groups; ++gg) {
@@ -370,7 +373,9 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #else
             if (more3) WAIT_VMCNT(4); else WAIT_VMCNT(0);
 #endif
+#ifndef EXP_NO_BARRIER
             BLOCK_BARRIER();
+#endif
         }
     }
 
