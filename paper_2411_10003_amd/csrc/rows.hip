@@ -82,19 +82,21 @@ __global__ __launch_bounds__(ROW_WAVES * 64) void scatter_rows_k_kernel(
 }
 
 // out[t,:] = sum_j w[t,j] * Yp[pos[t*k+j],:]   (fp32, ascending j, one rounding)
-template <typename ET>
+template <typename ET, int KT>
 __global__ __launch_bounds__(ROW_WAVES * 64) void combine_kernel(
     const ET* __restrict__ Yp, const int32_t* __restrict__ pos, const float* __restrict__ w,
-    ET* __restrict__ out, int T, int d, int k)
+    ET* __restrict__ out, int T, int d, int k_rt)
 {
     constexpr int VN = Vec<ET>::N;
+    constexpr int KMAX = KT ? KT : MAXK;
+    const int k = KT ? KT : k_rt;
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
     if (t >= T) return;
-    const uint4* src[MAXK];
-    float wj[MAXK];
+    const uint4* src[KMAX];
+    float wj[KMAX];
 #pragma unroll
-    for (int j = 0; j < MAXK; ++j) {
+    for (int j = 0; j < KMAX; ++j) {
         if (j < k) {
             src[j] = reinterpret_cast<const uint4*>(Yp + (size_t)pos[(size_t)t * k + j] * d);
             wj[j] = w[(size_t)t * k + j];
@@ -102,38 +104,51 @@ __global__ __launch_bounds__(ROW_WAVES * 64) void combine_kernel(
     }
     uint4* dst = reinterpret_cast<uint4*>(out + (size_t)t * d);
     const int nv = d / VN;
-    for (int v = lane; v < nv; v += 64) {
-        float acc[VN];
+    constexpr int U = (KT == 1 || KT == 2) ? 4 : 1;      // 16-byte pieces per lane requested before any is used
+    for (int v0 = lane; v0 < nv; v0 += 64 * U) {
+        uint4 raw[U][KMAX];
 #pragma unroll
-        for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int j = 0; j < MAXK; ++j) {
-            if (j < k) {
-                float y[VN];
-                Vec<ET>::unpack(src[j][v], y);
+            for (int j = 0; j < KMAX; ++j)
+                if (j < k && v0 + 64 * u < nv) raw[u][j] = src[j][v0 + 64 * u];
 #pragma unroll
-                for (int i = 0; i < VN; ++i) acc[i] = fmaf(wj[j], y[i], acc[i]);
+        for (int u = 0; u < U; ++u) {
+            if (v0 + 64 * u >= nv) break;
+            float acc[VN];
+#pragma unroll
+            for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j) {
+                if (j < k) {
+                    float y[VN];
+                    Vec<ET>::unpack(raw[u][j], y);
+#pragma unroll
+                    for (int i = 0; i < VN; ++i) acc[i] = fmaf(wj[j], y[i], acc[i]);
+                }
             }
+            dst[v0 + 64 * u] = Vec<ET>::pack(acc);
         }
-        dst[v] = Vec<ET>::pack(acc);
     }
 }
 
 // dYp[pos[a],:] = w[a] * dOut[t,:] ;  dw[t,j] = <dOut[t,:], Yp[pos[a],:]>
-template <typename ET>
+template <typename ET, int KT>
 __global__ __launch_bounds__(ROW_WAVES * 64) void combine_bwd_kernel(
     const ET* __restrict__ dOut, const ET* __restrict__ Yp, const int32_t* __restrict__ pos,
-    const float* __restrict__ w, ET* __restrict__ dYp, float* __restrict__ dw, int T, int d, int k)
+    const float* __restrict__ w, ET* __restrict__ dYp, float* __restrict__ dw, int T, int d, int k_rt)
 {
     constexpr int VN = Vec<ET>::N;
+    constexpr int KMAX = KT ? KT : MAXK;
+    const int k = KT ? KT : k_rt;
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
     if (t >= T) return;
-    const uint4* ysrc[MAXK];
-    uint4* gdst[MAXK];
-    float wj[MAXK], dot[MAXK];
+    const uint4* ysrc[KMAX];
+    uint4* gdst[KMAX];
+    float wj[KMAX], dot[KMAX];
 #pragma unroll
-    for (int j = 0; j < MAXK; ++j) {
+    for (int j = 0; j < KMAX; ++j) {
         dot[j] = 0.0f;
         if (j < k) {
             const size_t row = (size_t)pos[(size_t)t * k + j];
@@ -144,22 +159,37 @@ __global__ __launch_bounds__(ROW_WAVES * 64) void combine_bwd_kernel(
     }
     const uint4* gsrc = reinterpret_cast<const uint4*>(dOut + (size_t)t * d);
     const int nv = d / VN;
-    for (int v = lane; v < nv; v += 64) {
-        float g[VN];
-        Vec<ET>::unpack(gsrc[v], g);
+    constexpr int U = (KT == 1 || KT == 2) ? 2 : 1;
+    for (int v0 = lane; v0 < nv; v0 += 64 * U) {
+        uint4 graw[U], yraw[U][KMAX];
 #pragma unroll
-        for (int j = 0; j < MAXK; ++j) {
-            if (j < k) {
-                float y[VN], o[VN];
-                Vec<ET>::unpack(ysrc[j][v], y);
+        for (int u = 0; u < U; ++u) {
+            if (v0 + 64 * u < nv) {
+                graw[u] = gsrc[v0 + 64 * u];
 #pragma unroll
-                for (int i = 0; i < VN; ++i) { dot[j] = fmaf(g[i], y[i], dot[j]); o[i] = wj[j] * g[i]; }
-                gdst[j][v] = Vec<ET>::pack(o);
+                for (int j = 0; j < KMAX; ++j)
+                    if (j < k) yraw[u][j] = ysrc[j][v0 + 64 * u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (v0 + 64 * u >= nv) break;
+            float g[VN];
+            Vec<ET>::unpack(graw[u], g);
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j) {
+                if (j < k) {
+                    float y[VN], o[VN];
+                    Vec<ET>::unpack(yraw[u][j], y);
+#pragma unroll
+                    for (int i = 0; i < VN; ++i) { dot[j] = fmaf(g[i], y[i], dot[j]); o[i] = wj[j] * g[i]; }
+                    gdst[j][v0 + 64 * u] = Vec<ET>::pack(o);
+                }
             }
         }
     }
 #pragma unroll
-    for (int j = 0; j < MAXK; ++j) {
+    for (int j = 0; j < KMAX; ++j) {
         if (j < k) {
             const float s = wave_sum(dot[j]);
             if (lane == 0) dw[(size_t)t * k + j] = s;
@@ -168,34 +198,47 @@ __global__ __launch_bounds__(ROW_WAVES * 64) void combine_bwd_kernel(
 }
 
 // dX[t,:] = sum_j dXp[pos[t*k+j],:]
-template <typename ET>
+template <typename ET, int KT>
 __global__ __launch_bounds__(ROW_WAVES * 64) void dispatch_bwd_kernel(
-    const ET* __restrict__ dXp, const int32_t* __restrict__ pos, ET* __restrict__ dX, int T, int d, int k)
+    const ET* __restrict__ dXp, const int32_t* __restrict__ pos, ET* __restrict__ dX, int T, int d, int k_rt)
 {
     constexpr int VN = Vec<ET>::N;
+    constexpr int KMAX = KT ? KT : MAXK;
+    const int k = KT ? KT : k_rt;
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * ROW_WAVES + (threadIdx.x >> 6);
     if (t >= T) return;
-    const uint4* src[MAXK];
+    const uint4* src[KMAX];
 #pragma unroll
-    for (int j = 0; j < MAXK; ++j)
+    for (int j = 0; j < KMAX; ++j)
         if (j < k) src[j] = reinterpret_cast<const uint4*>(dXp + (size_t)pos[(size_t)t * k + j] * d);
     uint4* dst = reinterpret_cast<uint4*>(dX + (size_t)t * d);
     const int nv = d / VN;
-    for (int v = lane; v < nv; v += 64) {
-        float acc[VN];
+    constexpr int U = (KT == 1 || KT == 2) ? 4 : 1;
+    for (int v0 = lane; v0 < nv; v0 += 64 * U) {
+        uint4 raw[U][KMAX];
 #pragma unroll
-        for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int j = 0; j < MAXK; ++j) {
-            if (j < k) {
-                float y[VN];
-                Vec<ET>::unpack(src[j][v], y);
+            for (int j = 0; j < KMAX; ++j)
+                if (j < k && v0 + 64 * u < nv) raw[u][j] = src[j][v0 + 64 * u];
 #pragma unroll
-                for (int i = 0; i < VN; ++i) acc[i] += y[i];
+        for (int u = 0; u < U; ++u) {
+            if (v0 + 64 * u >= nv) break;
+            float acc[VN];
+#pragma unroll
+            for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j) {
+                if (j < k) {
+                    float y[VN];
+                    Vec<ET>::unpack(raw[u][j], y);
+#pragma unroll
+                    for (int i = 0; i < VN; ++i) acc[i] += y[i];
+                }
             }
+            dst[v0 + 64 * u] = Vec<ET>::pack(acc);
         }
-        dst[v] = Vec<ET>::pack(acc);
     }
 }
 
@@ -224,9 +267,13 @@ hipError_t launch_combine(const moe_shape_t& s, const void* Yp, const int32_t* p
     if (s.T == 0) return hipSuccess;
     const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
     if (s.dtype == MOE_F32)
-        hipLaunchKernelGGL(combine_kernel<float>, g, b, 0, st, (const float*)Yp, pos, w, (float*)out, s.T, s.d, s.k);
+        hipLaunchKernelGGL((combine_kernel<float, 0>), g, b, 0, st, (const float*)Yp, pos, w, (float*)out, s.T, s.d, s.k);
+    else if (s.k == 1)
+        hipLaunchKernelGGL((combine_kernel<bf16_t, 1>), g, b, 0, st, (const bf16_t*)Yp, pos, w, (bf16_t*)out, s.T, s.d, s.k);
+    else if (s.k == 2)
+        hipLaunchKernelGGL((combine_kernel<bf16_t, 2>), g, b, 0, st, (const bf16_t*)Yp, pos, w, (bf16_t*)out, s.T, s.d, s.k);
     else
-        hipLaunchKernelGGL(combine_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)Yp, pos, w, (bf16_t*)out, s.T, s.d, s.k);
+        hipLaunchKernelGGL((combine_kernel<bf16_t, 0>), g, b, 0, st, (const bf16_t*)Yp, pos, w, (bf16_t*)out, s.T, s.d, s.k);
     return hipGetLastError();
 }
 
@@ -236,10 +283,16 @@ hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void
     if (s.T == 0) return hipSuccess;
     const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
     if (s.dtype == MOE_F32)
-        hipLaunchKernelGGL(combine_bwd_kernel<float>, g, b, 0, st, (const float*)dOut, (const float*)Yp, pos, w,
+        hipLaunchKernelGGL((combine_bwd_kernel<float, 0>), g, b, 0, st, (const float*)dOut, (const float*)Yp, pos, w,
                            (float*)dYp, dw, s.T, s.d, s.k);
+    else if (s.k == 1)
+        hipLaunchKernelGGL((combine_bwd_kernel<bf16_t, 1>), g, b, 0, st, (const bf16_t*)dOut, (const bf16_t*)Yp, pos, w,
+                           (bf16_t*)dYp, dw, s.T, s.d, s.k);
+    else if (s.k == 2)
+        hipLaunchKernelGGL((combine_bwd_kernel<bf16_t, 2>), g, b, 0, st, (const bf16_t*)dOut, (const bf16_t*)Yp, pos, w,
+                           (bf16_t*)dYp, dw, s.T, s.d, s.k);
     else
-        hipLaunchKernelGGL(combine_bwd_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)dOut, (const bf16_t*)Yp, pos, w,
+        hipLaunchKernelGGL((combine_bwd_kernel<bf16_t, 0>), g, b, 0, st, (const bf16_t*)dOut, (const bf16_t*)Yp, pos, w,
                            (bf16_t*)dYp, dw, s.T, s.d, s.k);
     return hipGetLastError();
 }
@@ -249,8 +302,12 @@ hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int3
     if (s.T == 0) return hipSuccess;
     const dim3 g = row_grid(s.T), b(ROW_WAVES * 64);
     if (s.dtype == MOE_F32)
-        hipLaunchKernelGGL(dispatch_bwd_kernel<float>, g, b, 0, st, (const float*)dXp, pos, (float*)dX, s.T, s.d, s.k);
+        hipLaunchKernelGGL((dispatch_bwd_kernel<float, 0>), g, b, 0, st, (const float*)dXp, pos, (float*)dX, s.T, s.d, s.k);
+    else if (s.k == 1)
+        hipLaunchKernelGGL((dispatch_bwd_kernel<bf16_t, 1>), g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
+    else if (s.k == 2)
+        hipLaunchKernelGGL((dispatch_bwd_kernel<bf16_t, 2>), g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
     else
-        hipLaunchKernelGGL(dispatch_bwd_kernel<bf16_t>, g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
+        hipLaunchKernelGGL((dispatch_bwd_kernel<bf16_t, 0>), g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
     return hipGetLastError();
 }

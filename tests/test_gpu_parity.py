@@ -33,6 +33,7 @@ GATE_CASES = [
     _cfg(0),                                                  # the tiny fp32 configuration, complete
     _cfg(0, T=333, d=100, E=8, k=1, P=4),                     # fp32, column tail (d % 64 != 0)
     _cfg(1, T=1000, d=320, h=64),
+    _cfg(1, T=1001, d=512, h=64),                             # E = 16 fast path (LDS-streamed), ragged last block
     _cfg(2, T=777, d=256, h=64, E=32, k=2),
     _cfg(4, T=515, d=192, h=64, E=64, k=1, P=16),
     _cfg(1, T=300, d=128, h=64, E=100, k=3, P=10, n_replicas=1),
