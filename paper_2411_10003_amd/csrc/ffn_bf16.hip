@@ -60,8 +60,8 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
 __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
-// staged through a 4-deep ring of LDS buffers (16 KB per operand per slice).
-constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4, NT = 512;
+// staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5, NT = 512;
 #ifndef BAND
 #define BAND 8
 #endif
@@ -82,16 +82,24 @@ template <int COLS>
 __device__ __forceinline__ uint32_t kmajor_off(int krow, int col) { return krow * (COLS * 2) + ((((col >> 5) ^ (krow & 3))) << 6) + (col & 31) * 2; }
 
 // Fragment = 32 rows (or columns) x 16 contraction steps; lane l holds row l%32, steps 8*(l/32)..+7.
-__device__ __forceinline__ bf16x8 lds_frag_kcontig(uint32_t addr) { return *(LDS_PTR(bf16x8))(uintptr_t)addr; }
+// Fragment reads are issued as assembly and waited for by hand (WAIT_FRAGS below): the compiler's
+// own wait insertion cannot express "the set loaded one iteration ago is complete" and would stall
+// every MFMA group on the fragments that were only just requested for the next iteration.
+__device__ __forceinline__ void lds_frag_kcontig(bf16x8& f, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f) : "v"(addr));
+}
 // The transposing load works on blocks of 16 lanes: lane s of a block points at 4 consecutive columns
 // of step s/4; lane i of the block receives column i of steps 0..3.  Two loads give the 8 steps of a
 // lane in the same order as the K-contiguous fragment.
-__device__ __forceinline__ bf16x8 lds_frag_kmajor(uint32_t addr, uint32_t row4_bytes)
+template <int ROW4_BYTES>
+__device__ __forceinline__ void lds_frag_kmajor(bf16x8& f, uint32_t addr)
 {
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)addr);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(uintptr_t)(addr + row4_bytes));
+    s16x4 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3"
+                 : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(ROW4_BYTES));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
+    f = __builtin_bit_cast(bf16x8, v);
 }
 
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;     // raw buffer resource (4 scalar registers)
@@ -259,10 +267,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
 
     // Slices are requested strictly in order; the source offsets advance with the stream.
-    int iss_t = 0, iss_in_seg = 0, iss_seg = 0;
+    int iss_t = 0, iss_in_seg = 0, iss_seg = 0, iss_stage = 0;
     uint32_t soffA = 0, soffB = 0;
     auto issue_next = [&]() {                              // slice iss_t -> stage iss_t % STAGES
-        const uint32_t st = lds0 + (uint32_t)(iss_t & (STAGES - 1)) * STAGE_BYTES;
+        const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
+        iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
         const rsrc_t ra = iss_seg ? rA[1] : rA[0];
 #ifndef EXP_NO_A
         dma16(ra, st + ldsA[0], voffA[0], soffA);
@@ -311,16 +320,25 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 fb_addr[j] = OPER_BYTES + kmajor_off<BN>(krow, wn * WN + j * 32 + cofs);
         }
     }
-    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int t, int half) {
-        const uint32_t st = lds0 + (uint32_t)(t & (STAGES - 1)) * STAGE_BYTES;
+    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, int half) {
+        const uint32_t st = lds0 + (uint32_t)stage * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[i] = A_KMAJOR ? lds_frag_kmajor(st + fa_addr[i] + half * A_HALF, 4 * BM * 2)
-                             : lds_frag_kcontig(st + (fa_addr[i] ^ (half ? 32u : 0u)));
+        for (int i = 0; i < TM; ++i) {
+            if (A_KMAJOR) lds_frag_kmajor<4 * BM * 2>(fa[i], st + fa_addr[i] + half * A_HALF);
+            else lds_frag_kcontig(fa[i], st + (fa_addr[i] ^ (half ? 32u : 0u)));
+        }
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[j] = B_KMAJOR ? lds_frag_kmajor(st + fb_addr[j] + half * B_HALF, 4 * BCOLS * 2)
-                             : lds_frag_kcontig(st + (fb_addr[j] ^ (half ? 32u : 0u)));
+        for (int j = 0; j < TN; ++j) {
+            if (B_KMAJOR) lds_frag_kmajor<4 * BCOLS * 2>(fb[j], st + fb_addr[j] + half * B_HALF);
+            else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
+        }
+    };
+    // LDS returns in order, so "at most one set of reads outstanding" means every older set is complete.
+    constexpr int SET_READS = (A_KMAJOR ? 2 * TM : TM) + (B_KMAJOR ? 2 * TN : TN);
+    auto wait_frags = [&](bf16x8 (&)[TM], bf16x8 (&)[TN], bool newer_set_in_flight) {
+        if (newer_set_in_flight) asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(SET_READS) : "memory");
+        else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);                 // nothing (in particular no MFMA) moves above the wait
     };
 
     f32x16 acc[TM][TN];
@@ -341,41 +359,45 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 
     // ---- main loop.  Invariant: the barrier that ends iteration t-1 makes slice t+1 visible to
     // every wave, so the first fragments of slice t+1 are fetched before the barrier of iteration t
-    // and the matrix pipe never drains.  Slice t+3 is requested at the top of iteration t and must
-    // have landed when iteration t+1 ends: two iterations of latency cover.
+    // and the matrix pipe never drains.  Slice t+4 is requested at the top of iteration t (its ring
+    // slot held slice t-1) and must have landed when iteration t+2 ends: three iterations of
+    // latency cover, which keeps enough bytes in flight while the waves are busy multiplying.
     if (k_tiles > 0) {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         issue_next();
         if (k_tiles > 1) issue_next();
         if (k_tiles > 2) issue_next();
-        if (k_tiles > 2) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+        if (k_tiles > 3) issue_next();
+        if (k_tiles > 3) WAIT_VMCNT(8); else if (k_tiles > 2) WAIT_VMCNT(4); else WAIT_VMCNT(0);
         BLOCK_BARRIER();
         load_frags(fa0, fb0, 0, 0);
+        int cur = 0;                                       // ring slot of slice t
         for (int t = 0; t < k_tiles; ++t) {
-            const bool more3 = t + 3 < k_tiles;
+            const int nxt = (cur + 1 == STAGES) ? 0 : cur + 1;
+            const bool more = t + 1 < k_tiles;
 #ifndef EXP_NO_DMA
-            if (more3) issue_next();
+            if (t + 4 < k_tiles) issue_next();
 #endif
 #ifndef EXP_NO_LDS
-            load_frags(fa1, fb1, t, 1);
+            load_frags(fa1, fb1, cur, 1);                  // second half of slice t
+            wait_frags(fa0, fb0, true);                    // first half (requested before the last barrier)
 #endif
 #ifndef EXP_NO_MMA
             mma(fa0, fb0);
 #endif
 #ifndef EXP_NO_LDS
-            if (t + 1 < k_tiles) load_frags(fa0, fb0, t + 1, 0);
+            if (more) load_frags(fa0, fb0, nxt, 0);        // first half of slice t+1 (published one barrier ago)
+            wait_frags(fa1, fb1, more);
 #endif
 #ifndef EXP_NO_MMA
             mma(fa1, fb1);
 #endif
-#ifdef EXP_VM8
-            if (more3) WAIT_VMCNT(8); else WAIT_VMCNT(0);
-#else
-            if (more3) WAIT_VMCNT(4); else WAIT_VMCNT(0);
-#endif
+            // slice t+2 must be complete; t+3 and t+4 may still be in flight
+            if (t + 4 < k_tiles) WAIT_VMCNT(8); else if (t + 3 < k_tiles) WAIT_VMCNT(4); else WAIT_VMCNT(0);
 #ifndef EXP_NO_BARRIER
             BLOCK_BARRIER();
 #endif
+            cur = nxt;
         }
     }
 
