@@ -61,16 +61,21 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
-constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5, NT = 512;
+#ifndef GEMM_WGN
+#define GEMM_WGN 4          // waves along N: 4 -> 8 waves of 128 x 64, 2 -> 4 waves of 128 x 128
+#endif
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
 #ifndef BAND
 #define BAND 8
 #endif
-constexpr int WGM = 2, WGN = 4, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+constexpr int WGM = 2, WGN = GEMM_WGN, NWAVES = WGM * WGN, NT = NWAVES * 64;
+constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+constexpr int PIECES = 16 / NWAVES;         // 1-KB DMA pieces per wave per 16-KB operand slice
 constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
-constexpr int EP_PITCH = 64 * 4 + 16;       // epilogue patch: bytes per staged row of 64 floats (padded against bank conflicts)
+constexpr int EP_PITCH = WN * 4 + 16;       // epilogue patch: bytes per staged row of WN floats (padded against bank conflicts)
 constexpr int EP_WAVE = 64 * EP_PITCH;      // 64 rows per wave at a time
 constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_BYTES;
-constexpr size_t LDS_BYTES = RING_BYTES > (size_t)8 * EP_WAVE ? RING_BYTES : (size_t)8 * EP_WAVE;
+constexpr size_t LDS_BYTES = RING_BYTES > (size_t)NWAVES * EP_WAVE ? RING_BYTES : (size_t)NWAVES * EP_WAVE;
 
 // ---- LDS layouts (byte offsets inside one operand buffer) --------------------------------------
 // K-contiguous operand: [256 rows][32 steps], 64 bytes per row, 16-byte pieces XOR-swizzled by the
@@ -127,7 +132,7 @@ __device__ __forceinline__ void dma16(rsrc_t r, uint32_t lds_base, uint32_t voff
                  :: "s"(lds_base), "v"(voff), "s"(r), "s"(soff) : "memory");
 }
 
-#define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+#define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(n) : "memory")
 #define BLOCK_BARRIER() asm volatile("s_barrier" ::: "memory")
 
 // ---- the kernel ---------------------------------------------------------------------------------
@@ -237,8 +242,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             }
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int blk = wave + 8 * i;                  // piece index inside a 16-KB operand buffer
+        for (int i = 0; i < PIECES; ++i) {
+            const int blk = wave + NWAVES * i;             // piece index inside a 16-KB operand buffer
             const int L = blk * 64 + lane;                 // 16-byte slot inside the buffer
             ldsA[i] = blk * 1024;
             if (A_KMAJOR) {
@@ -253,9 +258,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 const int row = L >> 2, piece = (L & 3) ^ ((row >> 2) & 3);
                 voffB[i] = (uint32_t)((row * p.ldb + piece * 8) * 2);
             } else if (DUAL) {
-                // two sub-buffers of [32][128]; piece i of this wave belongs to half i
-                const int L2 = wave * 64 + lane;
-                ldsB[i] = i * 8192 + wave * 1024;
+                // two sub-buffers of [32][128] (8 pieces each); this wave's pieces alternate between them
+                const int half = i & 1, blk2 = wave + NWAVES * (i >> 1);
+                const int L2 = blk2 * 64 + lane;
+                ldsB[i] = half * 8192 + blk2 * 1024;
                 const int krow = L2 >> 4, pp = L2 & 15, col = (((pp >> 2) ^ (krow & 3)) << 5) + (pp & 3) * 8;
                 voffB[i] = (uint32_t)((krow * p.ldb + col) * 2);
             } else {
@@ -274,17 +280,17 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
         const rsrc_t ra = iss_seg ? rA[1] : rA[0];
 #ifndef EXP_NO_A
-        dma16(ra, st + ldsA[0], voffA[0], soffA);
-        dma16(ra, st + ldsA[1], voffA[1], soffA);
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) dma16(ra, st + ldsA[i], voffA[i], soffA);
 #endif
 #ifndef EXP_NO_B
         if (DUAL) {
-            dma16(rB[0], st + OPER_BYTES + ldsB[0], voffB[0], soffB);
-            dma16(rB[1], st + OPER_BYTES + ldsB[1], voffB[1], soffB);
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) dma16(rB[i & 1], st + OPER_BYTES + ldsB[i], voffB[i], soffB);
         } else {
             const rsrc_t rb = (KIND == KIND_NT && iss_seg) ? rB[1] : rB[0];
-            dma16(rb, st + OPER_BYTES + ldsB[0], voffB[0], soffB);
-            dma16(rb, st + OPER_BYTES + ldsB[1], voffB[1], soffB);
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) dma16(rb, st + OPER_BYTES + ldsB[i], voffB[i], soffB);
         }
 #endif
         ++iss_t; ++iss_in_seg;
@@ -333,9 +339,27 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
         }
     };
+    // fragment number n of a set: 0..TM-1 are A fragments, TM..TM+TN-1 are B fragments
+    auto load_frag_n = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, int half, int n) {
+        const uint32_t st = lds0 + (uint32_t)stage * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (i != n) continue;
+            if (A_KMAJOR) lds_frag_kmajor<4 * BM * 2>(fa[i], st + fa_addr[i] + half * A_HALF);
+            else lds_frag_kcontig(fa[i], st + (fa_addr[i] ^ (half ? 32u : 0u)));
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (TM + j != n) continue;
+            if (B_KMAJOR) lds_frag_kmajor<4 * BCOLS * 2>(fb[j], st + fb_addr[j] + half * B_HALF);
+            else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
+        }
+    };
     // LDS returns in order, so "at most one set of reads outstanding" means every older set is complete.
-    constexpr int SET_READS = (A_KMAJOR ? 2 * TM : TM) + (B_KMAJOR ? 2 * TN : TN);
+    constexpr int SET_READS_RAW = (A_KMAJOR ? 2 * TM : TM) + (B_KMAJOR ? 2 * TN : TN);
+    constexpr int SET_READS = SET_READS_RAW > 15 ? 15 : SET_READS_RAW;   // the counter saturates at 15
     auto wait_frags = [&](bf16x8 (&)[TM], bf16x8 (&)[TN], bool newer_set_in_flight) {
+        __builtin_amdgcn_sched_barrier(0);                 // earlier MFMAs stay above the wait
         if (newer_set_in_flight) asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(SET_READS) : "memory");
         else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);                 // nothing (in particular no MFMA) moves above the wait
@@ -349,13 +373,19 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+    // MFMAs number m0 .. m1-1 of the TM*TN products of one 16-step
+    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN], int m0_, int m1_) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        for (int m = 0; m < TM * TN; ++m) {
+            if (m < m0_ || m >= m1_) continue;
+            const int i = m / TN, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
     };
+#ifndef GEMM_LEAD
+#define GEMM_LEAD 4
+#endif
+    constexpr int LEAD = GEMM_LEAD;                                // MFMAs issued before the next fragment set is requested
 
     // ---- main loop.  Invariant: the barrier that ends iteration t-1 makes slice t+1 visible to
     // every wave, so the first fragments of slice t+1 are fetched before the barrier of iteration t
@@ -368,32 +398,58 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         if (k_tiles > 1) issue_next();
         if (k_tiles > 2) issue_next();
         if (k_tiles > 3) issue_next();
-        if (k_tiles > 3) WAIT_VMCNT(8); else if (k_tiles > 2) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+        if (k_tiles > 3) WAIT_VMCNT(4 * PIECES); else if (k_tiles > 2) WAIT_VMCNT(2 * PIECES); else WAIT_VMCNT(0);
         BLOCK_BARRIER();
         load_frags(fa0, fb0, 0, 0);
         int cur = 0;                                       // ring slot of slice t
         for (int t = 0; t < k_tiles; ++t) {
             const int nxt = (cur + 1 == STAGES) ? 0 : cur + 1;
             const bool more = t + 1 < k_tiles;
-#ifndef EXP_NO_DMA
+            // Each half starts by feeding the matrix pipe from the set that is already in registers; the
+            // requests for the next set (and the DMA of slice t+4) go out in the shadow of those MFMAs.
+#ifdef GEMM_SPREAD
+            // fragment requests of the next set are spread one or two per MFMA over the first MFMAs of a half
+            wait_frags(fa0, fb0, false);
+            mma(fa0, fb0, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
             if (t + 4 < k_tiles) issue_next();
-#endif
-#ifndef EXP_NO_LDS
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 1; m < TM * TN; ++m) {
+                mma(fa0, fb0, m, m + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * (m - 1) < TM + TN) load_frag_n(fa1, fb1, cur, 1, 2 * (m - 1));
+                if (2 * (m - 1) + 1 < TM + TN) load_frag_n(fa1, fb1, cur, 1, 2 * (m - 1) + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_frags(fa1, fb1, false);
+#pragma unroll
+            for (int m = 0; m < TM * TN; ++m) {
+                mma(fa1, fb1, m, m + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (more && m < (TM + TN + 1) / 2) {
+                    load_frag_n(fa0, fb0, nxt, 0, 2 * m);
+                    if (2 * m + 1 < TM + TN) load_frag_n(fa0, fb0, nxt, 0, 2 * m + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#else
+            wait_frags(fa0, fb0, false);                   // first half of slice t (requested before the last barrier)
+            mma(fa0, fb0, 0, LEAD);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 4 < k_tiles) issue_next();
             load_frags(fa1, fb1, cur, 1);                  // second half of slice t
-            wait_frags(fa0, fb0, true);                    // first half (requested before the last barrier)
-#endif
-#ifndef EXP_NO_MMA
-            mma(fa0, fb0);
-#endif
-#ifndef EXP_NO_LDS
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fa0, fb0, LEAD, TM * TN);
+            wait_frags(fa1, fb1, false);
+            mma(fa1, fb1, 0, LEAD);
+            __builtin_amdgcn_sched_barrier(0);
             if (more) load_frags(fa0, fb0, nxt, 0);        // first half of slice t+1 (published one barrier ago)
-            wait_frags(fa1, fb1, more);
-#endif
-#ifndef EXP_NO_MMA
-            mma(fa1, fb1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(fa1, fb1, LEAD, TM * TN);
 #endif
             // slice t+2 must be complete; t+3 and t+4 may still be in flight
-            if (t + 4 < k_tiles) WAIT_VMCNT(8); else if (t + 3 < k_tiles) WAIT_VMCNT(4); else WAIT_VMCNT(0);
+            if (t + 4 < k_tiles) WAIT_VMCNT(4 * PIECES); else if (t + 3 < k_tiles) WAIT_VMCNT(2 * PIECES); else WAIT_VMCNT(0);
 #ifndef EXP_NO_BARRIER
             BLOCK_BARRIER();
 #endif
@@ -410,7 +466,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     unsigned char* patch = smem + wave * EP_WAVE;
     const int lrow = lane & 31, lcol = (lane >> 5) * 4;
     const long row_limit = (KIND == KIND_TN) ? (long)p.Mout : a_row_end;
-    constexpr int CG = DUAL ? 4 : 8;                       // 8-column groups per staged row that carry outputs
+    constexpr int CG = DUAL ? WN / 16 : WN / 8;            // 8-column groups per staged row that carry outputs
     const int erow = lane / CG, ecg = lane % CG;
     constexpr int ROWS_PER_PASS = 64 / CG;
 #pragma unroll
@@ -437,13 +493,16 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             if (row >= row_limit || col >= p.N) continue;
             float v[8], u[8];
             {
-                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + ecg * 32);
-                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + ecg * 32 + 16);
+                // dual: fragments alternate x W1 / x W3, 32 columns each; group ecg sits in pair ecg/4
+                const int c0 = DUAL ? ((ecg >> 2) * 64 + (ecg & 3) * 8) * 4 : ecg * 32;
+                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + c0);
+                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + c0 + 16);
                 v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w; v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
             }
-            if (DUAL) {                                                    // columns 32.. of the patch hold x W3
-                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + 128 + ecg * 32);
-                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + 128 + ecg * 32 + 16);
+            if (DUAL) {                                                    // the next 32 columns of the patch hold x W3
+                const int c1 = ((ecg >> 2) * 64 + 32 + (ecg & 3) * 8) * 4;
+                const float4 x0 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + c1);
+                const float4 x1 = *reinterpret_cast<const float4*>(patch + r * EP_PITCH + c1 + 16);
                 u[0] = x0.x; u[1] = x0.y; u[2] = x0.z; u[3] = x0.w; u[4] = x1.x; u[5] = x1.y; u[6] = x1.z; u[7] = x1.w;
             }
             const long o = row * p.ldo + col;
