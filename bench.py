@@ -25,6 +25,9 @@ METRIC = "MoE-layer tokens/sec/GPU (gate+dispatch+grouped FFN+combine); FFN MFMA
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3        # fp32 vector
 PEAK_HBM_GBS = 8000.0          # HBM3E
+# HBM-side bytes of all grouped_gemm_kernel launches of one step, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
+# plain copy of known size (profiles/grouped_gemm_cfg3_pmc_traffic.txt); counters cannot be read from inside this run.
+MEASURED_FFN_TRAFFIC_BYTES = {3: 1.104e11}
 
 
 def log(*a):
@@ -89,6 +92,8 @@ def main():
     ap.add_argument("--iteration", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known size) to scale rocprofv3 FETCH_SIZE/WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is one GPU's share of the layer; it has no multi-GPU path (use --gpus 1)")
@@ -151,6 +156,12 @@ def main():
             hd.dispatch_bwd(b.dXp, b.layout.pos, b.dX); mark(8)
             hd.gate_bwd(b.dw, b.logits, b.idx, b.dlogits); mark(9)
 
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                                   # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -213,7 +224,7 @@ def main():
                                f"hosted groups={len(group_rows)} alpha={wl.alpha_for(cfg, args.iteration)}",
                    "pass": "fwd+bwd" if cfg.backward else "fwd", "hosted_rows_M": M, "assignments_A": A},
         "roofline": {"bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak, "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(cfg.index),
                      "kernel": "grouped_gemm_kernel (all launches of expert_ffn_fwd/bwd in a step)",
                      "flops_per_step": ffn_flops, "ms_per_step": ffn_ms},
         "per_call": per_call,
