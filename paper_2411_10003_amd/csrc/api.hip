@@ -30,6 +30,7 @@ int check_shape(const moe_shape_t& s)
     if (s.renorm != 0 && s.renorm != 1) return MOE_ERR_SHAPE;
     if ((long long)s.T * s.k >= (1ll << 31) / 2) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_BF16 && (s.d % 64 != 0 || s.h % 64 != 0)) return MOE_ERR_SHAPE;
+    if (s.dtype == MOE_BF16 && s.G > 64) return MOE_ERR_SHAPE;      // the grouped GEMM keeps one group per lane
     if (s.dtype == MOE_F32 && (s.d % 4 != 0)) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_F32 && (long long)s.T * s.k > 16ll * 65535) return MOE_ERR_SHAPE;
     return MOE_OK;

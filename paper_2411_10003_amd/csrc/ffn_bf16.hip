@@ -61,6 +61,8 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
+#define GEMM_PINGPONG 1
+#define GEMM_ACC_AGPR 1
 #ifndef GEMM_WGN
 #define GEMM_WGN 4          // waves along N: 4 -> 8 waves of 128 x 64, 2 -> 4 waves of 128 x 128
 #endif
@@ -135,6 +137,11 @@ __device__ __forceinline__ void dma16(rsrc_t r, uint32_t lds_base, uint32_t voff
 #define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(n) : "memory")
 #define BLOCK_BARRIER() asm volatile("s_barrier" ::: "memory")
 
+#ifdef GEMM_PROFILE
+__device__ unsigned long long g_prof[18 * 8 * 16];       // [KIND * 6 + EPI][wave][slot]              // [wave][phase] tick sums (working aid)
+#define PROF_T(x) const unsigned long long x = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0)
+#endif
+
 // ---- the kernel ---------------------------------------------------------------------------------
 template <int KIND, int EPI>
 __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
@@ -151,14 +158,41 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // ---- which tile.  Blocks go round-robin over the 8 XCDs (block b runs on XCD b % 8), each with
-    // its own L2, so XCD x takes a contiguous, equally sized share of the tiles that actually exist
-    // (the grid is an upper bound; the counts are only known here), and walks it in bands of 8 row
-    // tiles, column by column, so that the 32 tiles in flight on an XCD share operand slices.
+    // ---- group table, once per block: lane i of every wave holds hosted group i (at most 64 groups)
     int first_slot, n_groups;
     hosted_range(p.dest_slots, p.self, p.Gcap, first_slot, n_groups);
-    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    int g_row0 = 0, g_rows = 0;
+    if (lane < n_groups) {
+        g_row0 = p.slot_offsets[first_slot + lane];
+        g_rows = p.slot_offsets[first_slot + lane + 1] - g_row0;
+    }
+    const int g_nt = (g_rows + BM - 1) / BM;               // row tiles of the group (NN/NT)
+    int g_incl = g_nt;                                     // inclusive prefix over groups
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(g_incl, off, 64);
+        if (lane >= off) g_incl += up;
+    }
+    const int total_rt = __builtin_amdgcn_readlane(g_incl, 63);
+    const int g_excl = g_incl - g_nt;
 
+    // ---- which tiles.  The kernel is persistent: one block per CU walks its share of the tiles, so a
+    // tile's stores drain under the next tile's loads and nothing is relaunched.  Blocks go round-robin
+    // over the 8 XCDs (block b runs on XCD b % 8), each with its own L2; XCD x takes a contiguous,
+    // equally sized share of the tiles that actually exist (the counts are only known here) and its
+    // blocks walk it side by side in bands of 8 row tiles, column by column, so that the tiles in
+    // flight on an XCD share operand slices.
+    const int xcd = blockIdx.x & 7, q0 = blockIdx.x >> 3, q_stride = gridDim.x >> 3;
+    const int tiles_g = p.row_tiles * p.col_tiles;         // TN: tiles of one group
+    const int cg = (tiles_g + 7) >> 3;                     // TN: an eighth of them per XCD
+    const int n_act = total_rt * p.col_tiles;              // NN/NT: tiles that exist
+    const int per = (n_act + 7) >> 3;
+    const int q_end = (KIND == KIND_TN) ? p.Gcap * cg : per;
+
+  for (int q = q0; q < q_end; q += q_stride) {
+#ifdef GEMM_PROFILE
+    PROF_T(tile_t0_);
+#endif
     int g, rt, ct;
     long a_row0, a_row_end;      // valid rows of the A tile (NN/NT) or of the contraction (TN)
     int k_tiles;
@@ -166,42 +200,31 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     if (KIND == KIND_TN) {
         // every group has the same tile grid but its own contraction length: each XCD takes an
         // eighth of every group's tiles, so the work per XCD is balanced whatever the group sizes
-        const int tiles_g = p.row_tiles * p.col_tiles;
-        const int cg = (tiles_g + 7) >> 3;
         g = q / cg;
         const int t = xcd * cg + (q - g * cg);
-        if (g >= p.Gcap || t >= tiles_g) return;
+        if (t >= tiles_g) continue;
         const int band = t / (BAND * p.col_tiles);
         const int in_band = t - band * BAND * p.col_tiles;
         const int band_rows = min(BAND, p.row_tiles - band * BAND);
         rt = band * BAND + in_band % band_rows;
         ct = in_band / band_rows;
-        int row0 = 0, rows = 0;
-        if (g < n_groups) { row0 = p.slot_offsets[first_slot + g]; rows = p.slot_offsets[first_slot + g + 1] - row0; }
+        const int row0 = __builtin_amdgcn_readlane(g_row0, g & 63);       // empty for unused groups
+        const int rows = __builtin_amdgcn_readlane(g_rows, g & 63);
         a_row0 = row0; a_row_end = row0 + rows;
         k_tiles = (rows + BK - 1) / BK;
         m0 = rt * BM;
     } else {
-        int total_rt = 0;
-        for (int gg = 0; gg < n_groups; ++gg)
-            total_rt += (p.slot_offsets[first_slot + gg + 1] - p.slot_offsets[first_slot + gg] + BM - 1) / BM;
-        const int n_act = total_rt * p.col_tiles;
-        const int per = (n_act + 7) >> 3;
         const int t = xcd * per + q;
-        if (q >= per || t >= n_act) return;
+        if (t >= n_act) break;
         const int band = t / (BAND * p.col_tiles);
         const int in_band = t - band * BAND * p.col_tiles;
         const int band_rows = min(BAND, total_rt - band * BAND);
         rt = band * BAND + in_band % band_rows;
         ct = in_band / band_rows;
-        int acc = 0, gg = 0, row0 = 0, row_end = 0;
-        for (; gg < n_groups; ++gg) {
-            const int o = p.slot_offsets[first_slot + gg], e = p.slot_offsets[first_slot + gg + 1];
-            const int nt = (e - o + BM - 1) / BM;
-            if (rt < acc + nt) { row0 = o + (rt - acc) * BM; row_end = e; break; }
-            acc += nt;
-        }
-        g = gg;
+        g = __popcll(__ballot(g_incl <= rt)) & 63;                         // first group whose tiles reach past rt
+        const int gr0 = __builtin_amdgcn_readlane(g_row0, g);
+        const int row0 = gr0 + (rt - __builtin_amdgcn_readlane(g_excl, g)) * BM;
+        const int row_end = gr0 + __builtin_amdgcn_readlane(g_rows, g);
         a_row0 = row0; a_row_end = row_end;
         k_tiles = p.n_seg * (p.Kseg / BK);
         m0 = row0;
@@ -216,7 +239,14 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     uint32_t ldsA[2], ldsB[2];                             // LDS byte offsets of the pieces inside a stage
     uint32_t stepA, stepB;                                 // byte advance of the source per slice
     {
+#ifdef EXP_SAME_TILE
+        // timing experiment: every tile streams the operands of the first tile (outputs are meaningless)
+        const long a_rows = (KIND == KIND_TN) ? a_row_end - a_row0 : 256;
+        const long a_row0_keep = a_row0; const int n0_keep = n0, m0_keep = m0;
+        a_row0 = 0; const int n0 = 0; const int m0 = 0; (void)a_row0_keep; (void)n0_keep; (void)m0_keep;
+#else
         const long a_rows = a_row_end - a_row0;
+#endif
         if (KIND == KIND_TN) {
             rA[0] = rA[1] = make_rsrc(p.A[0] + a_row0 * p.lda + m0, (a_rows * p.lda - m0) * 2);
             rB[0] = rB[1] = make_rsrc(p.B[0] + a_row0 * p.ldb + n0, (a_rows * p.ldb - n0) * 2);
@@ -379,7 +409,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         for (int m = 0; m < TM * TN; ++m) {
             if (m < m0_ || m >= m1_) continue;
             const int i = m / TN, j = m % TN;
+#ifdef GEMM_ACC_AGPR
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i]));
+#else
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+#endif
         }
     };
 #ifndef GEMM_LEAD
@@ -392,6 +426,135 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     // and the matrix pipe never drains.  Slice t+4 is requested at the top of iteration t (its ring
     // slot held slice t-1) and must have landed when iteration t+2 ends: three iterations of
     // latency cover, which keeps enough bytes in flight while the waves are busy multiplying.
+#ifdef GEMM_PROFILE
+    PROF_T(tile_t1_);
+#endif
+#ifdef GEMM_PINGPONG
+    // ---- main loop, two phases per slice.  In its fetch phase a wave reads the fragments of slice t from
+    // LDS and requests its share of slice t+4; one barrier later, in its multiply phase, it issues the
+    // 16 MFMAs of the slice back to back.  The upper row of waves runs one barrier interval behind the
+    // lower one; waves w and w+4 share a SIMD, so while one of them feeds the matrix pipe the other
+    // collects its operands.  Fragment reads (bounded by LDS) and DMA requests (bounded by the address
+    // unit, about 16 cycles per instruction) alternate in the instruction stream so that both units
+    // work through the fetch phase side by side; a DMA request placed between MFMAs instead stalls the
+    // matrix pipe for several MFMA slots.
+    static_assert(WGN == 4 && PIECES == 2, "the interleave below is written for 8 waves");
+    if (k_tiles > 0) {
+        bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+        constexpr int L = STAGES - 1;                      // slices requested ahead
+        constexpr int SLICE_OPS = 2 * PIECES;              // DMA instructions of one wave per slice
+        auto wait_slices = [&](int n) {                    // at most n of this wave's slices still in flight
+            if (n >= 3) WAIT_VMCNT(3 * SLICE_OPS); else if (n == 2) WAIT_VMCNT(2 * SLICE_OPS);
+            else if (n == 1) WAIT_VMCNT(SLICE_OPS); else WAIT_VMCNT(0);
+        };
+        int t_dbg = 0;
+        auto issue_piece = [&](int n) {                    // n < PIECES: piece n of A, else piece n - PIECES of B
+            const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
+#ifdef EXP_NO_DMA
+            if (t_dbg > 8) return;
+#endif
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i) {
+                if (i == n) dma16(iss_seg ? rA[1] : rA[0], st + ldsA[i], voffA[i], soffA);
+                if (i + PIECES == n)
+                    dma16(DUAL ? rB[i & 1] : ((KIND == KIND_NT && iss_seg) ? rB[1] : rB[0]), st + OPER_BYTES + ldsB[i], voffB[i], soffB);
+            }
+        };
+        auto issue_advance = [&]() {
+            iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
+            ++iss_t; ++iss_in_seg;
+            soffA += stepA; soffB += stepB;
+            if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
+        };
+        issue_next();
+        if (k_tiles > 1) issue_next();
+        if (k_tiles > 2) issue_next();
+        if (k_tiles > 3) issue_next();
+        wait_slices(min(L, k_tiles) - 1);                  // slice 0 has landed
+        BLOCK_BARRIER();
+        if (wm == 1) BLOCK_BARRIER();
+        int cur = 0;
+#if GEMM_PROFILE > 1
+        unsigned long long pa[7] = {0, 0, 0, 0, 0, 0, 0};
+#endif
+        for (int t = 0; t < k_tiles; ++t) {
+#if GEMM_PROFILE > 1
+            PROF_T(q0_);
+#endif
+            // fetch phase.  Ring slot (t+4) % 5 held slice t-1, which every wave finished reading at
+            // least one barrier ago.
+            const bool request = t + L < k_tiles;
+            t_dbg = t;
+            // The four waves of a row place their block of DMA requests at four different points of
+            // the fragment reads, so the address unit sees one wave at a time and the other three
+            // keep LDS busy.
+            constexpr int NF = TM + TN;
+#pragma unroll
+            for (int n = 0; n <= 2 * NF; ++n) {
+                if (n % (2 * NF / 4 + 1) == 0 || n == 2 * NF) {
+                    const int slot = (n == 2 * NF) ? 3 : n / (2 * NF / 4 + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (request && wn == slot) {
+#pragma unroll
+                        for (int i = 0; i < SLICE_OPS; ++i) issue_piece(i);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#ifdef EXP_NO_LDS
+                if (t > 8) continue;
+#endif
+                if (n < NF) load_frag_n(fa0, fb0, cur, 0, n);
+                else if (n < 2 * NF) load_frag_n(fa1, fb1, cur, 1, n - NF);
+            }
+            if (request) issue_advance();
+#if GEMM_PROFILE > 1
+            __builtin_amdgcn_sched_barrier(0);
+            PROF_T(q1_);
+#endif
+            // this wave's pieces of slice t+1 must have landed before the barrier lets anyone read them
+            wait_slices(min(t + L, k_tiles - 1) - (t + 1));
+#if GEMM_PROFILE > 1
+            PROF_T(q2_);
+#endif
+            wait_frags(fa0, fb0, false);
+#if GEMM_PROFILE > 1
+            PROF_T(q3_);
+#endif
+            BLOCK_BARRIER();
+#if GEMM_PROFILE > 1
+            PROF_T(q4_);
+#endif
+            // multiply phase
+#ifndef EXP_NO_PRIO
+            __builtin_amdgcn_s_setprio(1);
+#endif
+#ifndef EXP_NO_MMA
+            mma(fa0, fb0, 0, TM * TN);
+            mma(fa1, fb1, 0, TM * TN);
+#else
+            mma(fa0, fb0, 0, 1);
+            mma(fa1, fb1, 0, 1);
+#endif
+#ifndef EXP_NO_PRIO
+            __builtin_amdgcn_s_setprio(0);
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+#if GEMM_PROFILE > 1
+            PROF_T(q5_);
+#endif
+            BLOCK_BARRIER();
+#if GEMM_PROFILE > 1
+            PROF_T(q6_);
+            pa[0] += q1_ - q0_; pa[1] += q2_ - q1_; pa[2] += q3_ - q2_; pa[3] += q4_ - q3_; pa[4] += q5_ - q4_; pa[5] += q6_ - q5_; pa[6] += 1;
+#endif
+            cur = (cur + 1 == STAGES) ? 0 : cur + 1;
+        }
+#if GEMM_PROFILE > 1
+        if (lane == 0) for (int i = 0; i < 7; ++i) atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + i], pa[i]);
+#endif
+        if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
+    }
+#else
     if (k_tiles > 0) {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         issue_next();
@@ -456,7 +619,14 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             cur = nxt;
         }
     }
+#endif
 
+#ifdef GEMM_ACC_AGPR
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");     // the last MFMAs have written back before the accumulators are read
+#endif
+#ifdef GEMM_PROFILE
+    PROF_T(tile_t2_);
+#endif
     // ---- epilogue.  A lane holds, per fragment, row l%32 and columns q*8 + (l/32)*4 + 0..3: storing
     // from there would touch 16-byte pieces of 32 different rows per instruction.  Instead every wave
     // passes its 128 x 64 accumulators through its own LDS patch (64 rows at a time, fp32) and reads
@@ -558,6 +728,15 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             }
         }
     }
+#ifdef GEMM_PROFILE
+    { PROF_T(tile_t3_); __syncthreads(); PROF_T(tile_t4_);
+      if (lane == 0) { atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 8], tile_t1_ - tile_t0_); atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 9], tile_t2_ - tile_t1_);
+                       atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 10], tile_t3_ - tile_t2_); atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 11], tile_t4_ - tile_t3_);
+                       atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 12], 1ull); } }
+#else
+    __syncthreads();             // every wave is done with its patch before the next tile's DMA lands there
+#endif
+  }
 }
 
 // ---- host side ----------------------------------------------------------------------------------
@@ -567,17 +746,22 @@ hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st
     constexpr bool DUAL = (EPI == EPI_FWD1_SWIGLU);
     const int bn = DUAL ? BN / 2 : BN;
     p.col_tiles = (p.N + bn - 1) / bn;
-    int grid;
     if (KIND == KIND_TN) {
         p.row_tiles = (p.Mout + BM - 1) / BM;
         p.n_tiles = n_groups_cap * p.row_tiles * p.col_tiles;
-        grid = 8 * n_groups_cap * ((p.row_tiles * p.col_tiles + 7) / 8);
     } else {
-        p.row_tiles = (rows_upper + BM - 1) / BM + n_groups_cap;      // upper bound of the row tiles
+        p.row_tiles = (rows_upper + BM - 1) / BM + n_groups_cap;      // upper bound; the kernel counts the real ones
         p.n_tiles = p.row_tiles * p.col_tiles;
-        grid = (p.n_tiles + 7) / 8 * 8;
     }
     if (p.n_tiles == 0) return hipSuccess;
+    static int cus = 0;                  // persistent: one block per CU (LDS allows no more), a multiple of 8
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+            n = 256;
+        cus = n / 8 * 8;
+    }
+    const int grid = cus;
     auto kern = grouped_gemm_kernel<KIND, EPI>;
     static bool configured = false;      // per instantiation
     if (!configured) {
@@ -599,6 +783,14 @@ GemmParams base_params(const moe_shape_t& s, const ffn_args& a)
 }
 
 }  // namespace
+
+#ifdef GEMM_PROFILE
+extern "C" int moe_debug_prof(unsigned long long* out, int reset)
+{
+    if (reset) { static unsigned long long z[18 * 128]; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)); }
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), 18 * 128 * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStream_t st)
 {

@@ -55,6 +55,8 @@ def test_create_validates_shapes(lib):
     assert create(d=100) == -2 and create(h=100) == -2            # bf16 needs multiples of 64
     assert create(dtype=0, d=34) == -2
     assert create(P=9) == -2 and create(self=4) == -2 and create(G=0) == -2 and create(G=9) == -2
+    assert create(E=128, G=64) == 0 and create(E=128, G=65) == -2    # bf16: at most 64 hosted groups
+    assert create(dtype=0, E=128, G=65) == 0
     assert create(dtype=7) == -5 and create(act=3) == -2 and create(renorm=2) == -2
     assert create(T=0) == -2
     assert lib.moe_create(None, None) == -1
