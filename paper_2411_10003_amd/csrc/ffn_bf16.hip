@@ -8,18 +8,20 @@
 //   bwd2  dXp   = dZ W1^T (+ dU W3^T)
 //   wgrad dW1 = Xp^T dZ, dW3 = Xp^T dU, dW2 = Act^T dYp over the rows of each group
 // Groups are ragged and may be empty; row tiles start at the group's first row and the last one
-// is masked, so nothing is padded to the largest load.  The grid is sized from an upper bound
-// of the tile count (the host never reads the counts); surplus blocks exit at once.
+// is masked, so nothing is padded to the largest load.  The kernel is persistent: one block per
+// CU walks its share of the tiles, which it derives on the device from the group offsets (the
+// host never reads the counts).
 //
 // Tiling: 256 x 256 output tile per block, 32-deep contraction slices moved from HBM/L2 straight
-// into a 4-deep ring of LDS buffers by buffer loads (no register staging; rows outside a ragged
-// group arrive as zeros because they lie past the end of the buffer resource), 32x32x16 bf16 MFMA.
-// An operand whose contraction index is contiguous in memory is kept row-major in LDS and read
-// with 16-byte loads; one whose contraction index is the slow one is kept as it is and read with
-// the transposing LDS load, so no operand is ever transposed in HBM.  Both layouts are
-// XOR-swizzled so that fragment reads are free of bank conflicts.  The MFMA is issued with the
-// operands swapped, which leaves every lane with four consecutive output columns of one row and
-// gives 8/16-byte stores.
+// into a 5-deep ring of LDS buffers by buffer loads (no register staging; rows outside a ragged
+// group arrive as zeros because they lie past the end of the buffer resource), 32x32x16 bf16 MFMA
+// with the accumulators in AGPRs.  An operand whose contraction index is contiguous in memory is
+// kept row-major in LDS and read with 16-byte loads; one whose contraction index is the slow one
+// is kept as it is and read with the transposing LDS load, so no operand is ever transposed in
+// HBM.  Both layouts are XOR-swizzled so that fragment reads are free of bank conflicts.  The MFMA
+// is issued with the operands swapped, which leaves every lane with four consecutive output
+// columns of one row.  The two rows of waves of a block alternate between fetching fragments and
+// multiplying, half an iteration apart.
 #include "internal.h"
 
 namespace {
@@ -61,16 +63,11 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
-#define GEMM_PINGPONG 1
-#define GEMM_ACC_AGPR 1
-#ifndef GEMM_WGN
-#define GEMM_WGN 4          // waves along N: 4 -> 8 waves of 128 x 64, 2 -> 4 waves of 128 x 128
-#endif
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
 #ifndef BAND
 #define BAND 8
 #endif
-constexpr int WGM = 2, WGN = GEMM_WGN, NWAVES = WGM * WGN, NT = NWAVES * 64;
+constexpr int WGM = 2, WGN = 4, NWAVES = WGM * WGN, NT = NWAVES * 64;
 constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
 constexpr int PIECES = 16 / NWAVES;         // 1-KB DMA pieces per wave per 16-KB operand slice
 constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
@@ -137,10 +134,6 @@ __device__ __forceinline__ void dma16(rsrc_t r, uint32_t lds_base, uint32_t voff
 #define WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(n) : "memory")
 #define BLOCK_BARRIER() asm volatile("s_barrier" ::: "memory")
 
-#ifdef GEMM_PROFILE
-__device__ unsigned long long g_prof[18 * 8 * 16];       // [KIND * 6 + EPI][wave][slot]              // [wave][phase] tick sums (working aid)
-#define PROF_T(x) const unsigned long long x = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0)
-#endif
 
 // ---- the kernel ---------------------------------------------------------------------------------
 template <int KIND, int EPI>
@@ -190,9 +183,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     const int q_end = (KIND == KIND_TN) ? p.Gcap * cg : per;
 
   for (int q = q0; q < q_end; q += q_stride) {
-#ifdef GEMM_PROFILE
-    PROF_T(tile_t0_);
-#endif
     int g, rt, ct;
     long a_row0, a_row_end;      // valid rows of the A tile (NN/NT) or of the contraction (TN)
     int k_tiles;
@@ -239,14 +229,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     uint32_t ldsA[2], ldsB[2];                             // LDS byte offsets of the pieces inside a stage
     uint32_t stepA, stepB;                                 // byte advance of the source per slice
     {
-#ifdef EXP_SAME_TILE
-        // timing experiment: every tile streams the operands of the first tile (outputs are meaningless)
-        const long a_rows = (KIND == KIND_TN) ? a_row_end - a_row0 : 256;
-        const long a_row0_keep = a_row0; const int n0_keep = n0, m0_keep = m0;
-        a_row0 = 0; const int n0 = 0; const int m0 = 0; (void)a_row0_keep; (void)n0_keep; (void)m0_keep;
-#else
         const long a_rows = a_row_end - a_row0;
-#endif
         if (KIND == KIND_TN) {
             rA[0] = rA[1] = make_rsrc(p.A[0] + a_row0 * p.lda + m0, (a_rows * p.lda - m0) * 2);
             rB[0] = rB[1] = make_rsrc(p.B[0] + a_row0 * p.ldb + n0, (a_rows * p.ldb - n0) * 2);
@@ -309,11 +292,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
         iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
         const rsrc_t ra = iss_seg ? rA[1] : rA[0];
-#ifndef EXP_NO_A
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) dma16(ra, st + ldsA[i], voffA[i], soffA);
-#endif
-#ifndef EXP_NO_B
         if (DUAL) {
 #pragma unroll
             for (int i = 0; i < PIECES; ++i) dma16(rB[i & 1], st + OPER_BYTES + ldsB[i], voffB[i], soffB);
@@ -322,7 +302,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int i = 0; i < PIECES; ++i) dma16(rb, st + OPER_BYTES + ldsB[i], voffB[i], soffB);
         }
-#endif
         ++iss_t; ++iss_in_seg;
         soffA += stepA; soffB += stepB;
         if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
@@ -369,30 +348,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
         }
     };
-    // fragment number n of a set: 0..TM-1 are A fragments, TM..TM+TN-1 are B fragments
-    auto load_frag_n = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, int half, int n) {
-        const uint32_t st = lds0 + (uint32_t)stage * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (i != n) continue;
-            if (A_KMAJOR) lds_frag_kmajor<4 * BM * 2>(fa[i], st + fa_addr[i] + half * A_HALF);
-            else lds_frag_kcontig(fa[i], st + (fa_addr[i] ^ (half ? 32u : 0u)));
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if (TM + j != n) continue;
-            if (B_KMAJOR) lds_frag_kmajor<4 * BCOLS * 2>(fb[j], st + fb_addr[j] + half * B_HALF);
-            else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
-        }
-    };
-    // LDS returns in order, so "at most one set of reads outstanding" means every older set is complete.
-    constexpr int SET_READS_RAW = (A_KMAJOR ? 2 * TM : TM) + (B_KMAJOR ? 2 * TN : TN);
-    constexpr int SET_READS = SET_READS_RAW > 15 ? 15 : SET_READS_RAW;   // the counter saturates at 15
-    auto wait_frags = [&](bf16x8 (&)[TM], bf16x8 (&)[TN], bool newer_set_in_flight) {
-        __builtin_amdgcn_sched_barrier(0);                 // earlier MFMAs stay above the wait
-        if (newer_set_in_flight) asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(SET_READS) : "memory");
-        else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);                 // nothing (in particular no MFMA) moves above the wait
+    auto wait_frags = [&]() {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);                 // no MFMA moves above the wait
     };
 
     f32x16 acc[TM][TN];
@@ -403,42 +362,25 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // MFMAs number m0 .. m1-1 of the TM*TN products of one 16-step
-    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN], int m0_, int m1_) {
+    // the TM*TN products of one 16-step.  The accumulators are pinned to AGPRs, which leaves the
+    // VGPRs of the wave to fragments and addresses.
+    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
 #pragma unroll
-        for (int m = 0; m < TM * TN; ++m) {
-            if (m < m0_ || m >= m1_) continue;
-            const int i = m / TN, j = m % TN;
-#ifdef GEMM_ACC_AGPR
-            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i]));
-#else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-#endif
-        }
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i]));
     };
-#ifndef GEMM_LEAD
-#define GEMM_LEAD 4
-#endif
-    constexpr int LEAD = GEMM_LEAD;                                // MFMAs issued before the next fragment set is requested
 
-    // ---- main loop.  Invariant: the barrier that ends iteration t-1 makes slice t+1 visible to
-    // every wave, so the first fragments of slice t+1 are fetched before the barrier of iteration t
-    // and the matrix pipe never drains.  Slice t+4 is requested at the top of iteration t (its ring
-    // slot held slice t-1) and must have landed when iteration t+2 ends: three iterations of
-    // latency cover, which keeps enough bytes in flight while the waves are busy multiplying.
-#ifdef GEMM_PROFILE
-    PROF_T(tile_t1_);
-#endif
-#ifdef GEMM_PINGPONG
-    // ---- main loop, two phases per slice.  In its fetch phase a wave reads the fragments of slice t from
-    // LDS and requests its share of slice t+4; one barrier later, in its multiply phase, it issues the
-    // 16 MFMAs of the slice back to back.  The upper row of waves runs one barrier interval behind the
-    // lower one; waves w and w+4 share a SIMD, so while one of them feeds the matrix pipe the other
-    // collects its operands.  Fragment reads (bounded by LDS) and DMA requests (bounded by the address
-    // unit, about 16 cycles per instruction) alternate in the instruction stream so that both units
-    // work through the fetch phase side by side; a DMA request placed between MFMAs instead stalls the
-    // matrix pipe for several MFMA slots.
-    static_assert(WGN == 4 && PIECES == 2, "the interleave below is written for 8 waves");
+    // ---- main loop, two phases per slice.  In its fetch phase a wave reads the fragments of slice t
+    // from LDS and requests its share of slice t+4; one barrier later, in its multiply phase, it issues
+    // the 16 MFMAs of the slice back to back.  The upper row of waves runs one barrier interval behind
+    // the lower one; waves w and w+4 share a SIMD, so while one of them feeds the matrix pipe the other
+    // collects its operands.  With LDS reads and MFMAs alone this loop runs at the MFMA rate; what it
+    // waits for in practice is the delivery of the slices from L2/HBM.  All fragment reads are issued
+    // before the DMA requests so that a request held up by the memory system never delays them (a
+    // request placed between MFMAs stalls the matrix pipe for several MFMA slots instead).
+    static_assert(WGN == 4 && PIECES == 2, "the loop is written for 8 waves");
     if (k_tiles > 0) {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         constexpr int L = STAGES - 1;                      // slices requested ahead
@@ -446,25 +388,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         auto wait_slices = [&](int n) {                    // at most n of this wave's slices still in flight
             if (n >= 3) WAIT_VMCNT(3 * SLICE_OPS); else if (n == 2) WAIT_VMCNT(2 * SLICE_OPS);
             else if (n == 1) WAIT_VMCNT(SLICE_OPS); else WAIT_VMCNT(0);
-        };
-        int t_dbg = 0;
-        auto issue_piece = [&](int n) {                    // n < PIECES: piece n of A, else piece n - PIECES of B
-            const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
-#ifdef EXP_NO_DMA
-            if (t_dbg > 8) return;
-#endif
-#pragma unroll
-            for (int i = 0; i < PIECES; ++i) {
-                if (i == n) dma16(iss_seg ? rA[1] : rA[0], st + ldsA[i], voffA[i], soffA);
-                if (i + PIECES == n)
-                    dma16(DUAL ? rB[i & 1] : ((KIND == KIND_NT && iss_seg) ? rB[1] : rB[0]), st + OPER_BYTES + ldsB[i], voffB[i], soffB);
-            }
-        };
-        auto issue_advance = [&]() {
-            iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
-            ++iss_t; ++iss_in_seg;
-            soffA += stepA; soffB += stepB;
-            if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
         };
         issue_next();
         if (k_tiles > 1) issue_next();
@@ -474,159 +397,30 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         BLOCK_BARRIER();
         if (wm == 1) BLOCK_BARRIER();
         int cur = 0;
-#if GEMM_PROFILE > 1
-        unsigned long long pa[7] = {0, 0, 0, 0, 0, 0, 0};
-#endif
         for (int t = 0; t < k_tiles; ++t) {
-#if GEMM_PROFILE > 1
-            PROF_T(q0_);
-#endif
             // fetch phase.  Ring slot (t+4) % 5 held slice t-1, which every wave finished reading at
             // least one barrier ago.
-            const bool request = t + L < k_tiles;
-            t_dbg = t;
-            // The four waves of a row place their block of DMA requests at four different points of
-            // the fragment reads, so the address unit sees one wave at a time and the other three
-            // keep LDS busy.
-            constexpr int NF = TM + TN;
-#pragma unroll
-            for (int n = 0; n <= 2 * NF; ++n) {
-                if (n % (2 * NF / 4 + 1) == 0 || n == 2 * NF) {
-                    const int slot = (n == 2 * NF) ? 3 : n / (2 * NF / 4 + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (request && wn == slot) {
-#pragma unroll
-                        for (int i = 0; i < SLICE_OPS; ++i) issue_piece(i);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#ifdef EXP_NO_LDS
-                if (t > 8) continue;
-#endif
-                if (n < NF) load_frag_n(fa0, fb0, cur, 0, n);
-                else if (n < 2 * NF) load_frag_n(fa1, fb1, cur, 1, n - NF);
-            }
-            if (request) issue_advance();
-#if GEMM_PROFILE > 1
+            load_frags(fa0, fb0, cur, 0);
+            load_frags(fa1, fb1, cur, 1);
             __builtin_amdgcn_sched_barrier(0);
-            PROF_T(q1_);
-#endif
+            if (t + L < k_tiles) issue_next();
             // this wave's pieces of slice t+1 must have landed before the barrier lets anyone read them
             wait_slices(min(t + L, k_tiles - 1) - (t + 1));
-#if GEMM_PROFILE > 1
-            PROF_T(q2_);
-#endif
-            wait_frags(fa0, fb0, false);
-#if GEMM_PROFILE > 1
-            PROF_T(q3_);
-#endif
+            wait_frags();
             BLOCK_BARRIER();
-#if GEMM_PROFILE > 1
-            PROF_T(q4_);
-#endif
             // multiply phase
-#ifndef EXP_NO_PRIO
             __builtin_amdgcn_s_setprio(1);
-#endif
-#ifndef EXP_NO_MMA
-            mma(fa0, fb0, 0, TM * TN);
-            mma(fa1, fb1, 0, TM * TN);
-#else
-            mma(fa0, fb0, 0, 1);
-            mma(fa1, fb1, 0, 1);
-#endif
-#ifndef EXP_NO_PRIO
+            mma(fa0, fb0);
+            mma(fa1, fb1);
             __builtin_amdgcn_s_setprio(0);
-#endif
             __builtin_amdgcn_sched_barrier(0);
-#if GEMM_PROFILE > 1
-            PROF_T(q5_);
-#endif
             BLOCK_BARRIER();
-#if GEMM_PROFILE > 1
-            PROF_T(q6_);
-            pa[0] += q1_ - q0_; pa[1] += q2_ - q1_; pa[2] += q3_ - q2_; pa[3] += q4_ - q3_; pa[4] += q5_ - q4_; pa[5] += q6_ - q5_; pa[6] += 1;
-#endif
             cur = (cur + 1 == STAGES) ? 0 : cur + 1;
         }
-#if GEMM_PROFILE > 1
-        if (lane == 0) for (int i = 0; i < 7; ++i) atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + i], pa[i]);
-#endif
         if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
     }
-#else
-    if (k_tiles > 0) {
-        bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-        issue_next();
-        if (k_tiles > 1) issue_next();
-        if (k_tiles > 2) issue_next();
-        if (k_tiles > 3) issue_next();
-        if (k_tiles > 3) WAIT_VMCNT(4 * PIECES); else if (k_tiles > 2) WAIT_VMCNT(2 * PIECES); else WAIT_VMCNT(0);
-        BLOCK_BARRIER();
-        load_frags(fa0, fb0, 0, 0);
-        int cur = 0;                                       // ring slot of slice t
-        for (int t = 0; t < k_tiles; ++t) {
-            const int nxt = (cur + 1 == STAGES) ? 0 : cur + 1;
-            const bool more = t + 1 < k_tiles;
-            // Each half starts by feeding the matrix pipe from the set that is already in registers; the
-            // requests for the next set (and the DMA of slice t+4) go out in the shadow of those MFMAs.
-#ifdef GEMM_SPREAD
-            // fragment requests of the next set are spread one or two per MFMA over the first MFMAs of a half
-            wait_frags(fa0, fb0, false);
-            mma(fa0, fb0, 0, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 4 < k_tiles) issue_next();
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int m = 1; m < TM * TN; ++m) {
-                mma(fa0, fb0, m, m + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (2 * (m - 1) < TM + TN) load_frag_n(fa1, fb1, cur, 1, 2 * (m - 1));
-                if (2 * (m - 1) + 1 < TM + TN) load_frag_n(fa1, fb1, cur, 1, 2 * (m - 1) + 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            wait_frags(fa1, fb1, false);
-#pragma unroll
-            for (int m = 0; m < TM * TN; ++m) {
-                mma(fa1, fb1, m, m + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (more && m < (TM + TN + 1) / 2) {
-                    load_frag_n(fa0, fb0, nxt, 0, 2 * m);
-                    if (2 * m + 1 < TM + TN) load_frag_n(fa0, fb0, nxt, 0, 2 * m + 1);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#else
-            wait_frags(fa0, fb0, false);                   // first half of slice t (requested before the last barrier)
-            mma(fa0, fb0, 0, LEAD);
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + 4 < k_tiles) issue_next();
-            load_frags(fa1, fb1, cur, 1);                  // second half of slice t
-            __builtin_amdgcn_sched_barrier(0);
-            mma(fa0, fb0, LEAD, TM * TN);
-            wait_frags(fa1, fb1, false);
-            mma(fa1, fb1, 0, LEAD);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more) load_frags(fa0, fb0, nxt, 0);        // first half of slice t+1 (published one barrier ago)
-            __builtin_amdgcn_sched_barrier(0);
-            mma(fa1, fb1, LEAD, TM * TN);
-#endif
-            // slice t+2 must be complete; t+3 and t+4 may still be in flight
-            if (t + 4 < k_tiles) WAIT_VMCNT(4 * PIECES); else if (t + 3 < k_tiles) WAIT_VMCNT(2 * PIECES); else WAIT_VMCNT(0);
-#ifndef EXP_NO_BARRIER
-            BLOCK_BARRIER();
-#endif
-            cur = nxt;
-        }
-    }
-#endif
 
-#ifdef GEMM_ACC_AGPR
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");     // the last MFMAs have written back before the accumulators are read
-#endif
-#ifdef GEMM_PROFILE
-    PROF_T(tile_t2_);
-#endif
     // ---- epilogue.  A lane holds, per fragment, row l%32 and columns q*8 + (l/32)*4 + 0..3: storing
     // from there would touch 16-byte pieces of 32 different rows per instruction.  Instead every wave
     // passes its 128 x 64 accumulators through its own LDS patch (64 rows at a time, fp32) and reads
@@ -639,6 +433,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     constexpr int CG = DUAL ? WN / 16 : WN / 8;            // 8-column groups per staged row that carry outputs
     const int erow = lane / CG, ecg = lane % CG;
     constexpr int ROWS_PER_PASS = 64 / CG;
+    constexpr bool BWD1 = (EPI == EPI_BWD1_GELU || EPI == EPI_BWD1_SWIGLU);
+    constexpr int N_PASS = 64 / ROWS_PER_PASS;
 #pragma unroll
     for (int half = 0; half < TM / 2; ++half) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -655,8 +451,27 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
+        // the saved pre-activations of a batch of passes are requested at once, so that their latency
+        // is paid once per batch and not once per pass
+        constexpr int BATCH = (EPI == EPI_BWD1_SWIGLU) ? 4 : N_PASS;
 #pragma unroll
-        for (int pass = 0; pass < 64 / ROWS_PER_PASS; ++pass) {
+        for (int pb = 0; pb < N_PASS; pb += BATCH) {
+        uint4 zin[BWD1 ? BATCH : 1], uin[EPI == EPI_BWD1_SWIGLU ? BATCH : 1];
+        if (BWD1) {
+#pragma unroll
+            for (int k = 0; k < BATCH; ++k) {
+                const long row = (long)m0 + wm * WM + half * 64 + (pb + k) * ROWS_PER_PASS + erow;
+                const int col = n0 + wn * WN + ecg * 8;
+                zin[k] = make_uint4(0, 0, 0, 0);
+                if (EPI == EPI_BWD1_SWIGLU) uin[k] = make_uint4(0, 0, 0, 0);
+                if (row < row_limit && col < p.N) {
+                    zin[k] = *reinterpret_cast<const uint4*>(p.Zin + row * p.ldo + col);
+                    if (EPI == EPI_BWD1_SWIGLU) uin[k] = *reinterpret_cast<const uint4*>(p.Uin + row * p.ldo + col);
+                }
+            }
+        }
+#pragma unroll
+        for (int pass = pb; pass < pb + BATCH; ++pass) {
             const int r = pass * ROWS_PER_PASS + erow;                     // row inside the 64-row patch
             const long row = (long)m0 + wm * WM + half * 64 + r;
             const int col = n0 + (DUAL ? wn * (WN / 2) : wn * WN) + ecg * 8;
@@ -706,15 +521,15 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             } else if (EPI == EPI_BWD1_GELU) {
                 float z[8], dz[8], a[8];
-                unpack8(*reinterpret_cast<const uint4*>(p.Zin + o), z);
+                unpack8(zin[pass - pb], z);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { dz[e] = v[e] * gelu_grad_f(z[e]); a[e] = gelu_f(z[e]); }
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             } else if (EPI == EPI_BWD1_SWIGLU) {
                 float z[8], uu[8], dz[8], du[8], a[8];
-                unpack8(*reinterpret_cast<const uint4*>(p.Zin + o), z);
-                unpack8(*reinterpret_cast<const uint4*>(p.Uin + o), uu);
+                unpack8(zin[pass - pb], z);
+                unpack8(uin[pass - pb], uu);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float sg = sigmoid_f(z[e]);
@@ -727,15 +542,9 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             }
         }
+        }
     }
-#ifdef GEMM_PROFILE
-    { PROF_T(tile_t3_); __syncthreads(); PROF_T(tile_t4_);
-      if (lane == 0) { atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 8], tile_t1_ - tile_t0_); atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 9], tile_t2_ - tile_t1_);
-                       atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 10], tile_t3_ - tile_t2_); atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 11], tile_t4_ - tile_t3_);
-                       atomicAdd(&g_prof[((KIND * 6 + EPI) * 8 + wave) * 16 + 12], 1ull); } }
-#else
     __syncthreads();             // every wave is done with its patch before the next tile's DMA lands there
-#endif
   }
 }
 
@@ -784,13 +593,6 @@ GemmParams base_params(const moe_shape_t& s, const ffn_args& a)
 
 }  // namespace
 
-#ifdef GEMM_PROFILE
-extern "C" int moe_debug_prof(unsigned long long* out, int reset)
-{
-    if (reset) { static unsigned long long z[18 * 128]; return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof(z)); }
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_prof), 18 * 128 * sizeof(unsigned long long));
-}
-#endif
 
 hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStream_t st)
 {
