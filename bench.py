@@ -216,6 +216,33 @@ def main():
             e.update({"TFLOP/s": round(2 * fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
         per_call[c] = e
 
+    # the planner (Algorithm 1) on the P x E count matrix of this batch: not one of the timed calls of a step
+    # (the paper runs it under the all-to-all of the previous iteration), reported beside them
+    gating_np = wl.make_gating(cfg, counts, args.iteration)
+    gating = torch.from_numpy(gating_np).to(dev)
+    pc = wl.planner_constants(cfg)
+    pbuf = binding.PlanBuffers(cfg.P, cfg.E, dev)
+    plan_args = dict(n=1, overlap=False, alpha=1.0, **pc)
+    binding.plan(gating, pbuf, **plan_args)
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    for _ in range(20):
+        binding.plan(gating, pbuf, **plan_args)
+    pe[1].record()
+    torch.cuda.synchronize()
+    info = pbuf.info.cpu().numpy()
+    ptimes = pbuf.times.cpu().numpy()
+    per_call["plan"] = {"ms": round(pe[0].elapsed_time(pe[1]) / 20, 4), "in_step": False, "selected": int(info[1]),
+                        "kept": int(info[0]), "model_T_before_s": float(ptimes[0]), "model_T_after_s": float(ptimes[1]),
+                        "gating": f"{cfg.P}x{cfg.E} counts, n=1, Eq. 7"}
+    if not args.no_cpu_baseline:
+        from oracle import planner_oracle as po
+        t0 = time.perf_counter()
+        ref = po.greedy_search(gating_np.astype(np.int64), 1, po.PlannerModel(alpha=1.0, overlap=False, **pc))
+        per_call["plan"]["oracle_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+        assert ref["cnt"] == int(info[0]) and ref["T_output"] == float(ptimes[1]), "planner disagrees with its oracle"
+
     result = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,

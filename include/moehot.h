@@ -168,6 +168,58 @@ int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* 
 int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int32_t* idx,
                  float* dlogits, void* stream);
 
+/* ---- planner (Sections 4.2-4.3 and 5.3 of the paper) ------------------------------------------
+ *
+ * moe_plan runs the paper's greedy search for a lightweight expert placement (Algorithm 1) on the
+ * GPU, in one wavefront, from the matrix of routing counts of all devices, so that the plan of the
+ * next iteration can be produced without the host reading any counts.  A placement is evaluated
+ * with the performance model T'(R, H, s, n) = 4 T_A2A(R) + 3 T_FEC(H) + T_Trans(s, n) + T_Agg(s, n)
+ * (Eqs. 1-7) or, with overlap = 1, with Trans and Agg reduced by the computation the scheduler hides
+ * them behind (Eq. 8); the search runs while max(H) - min(H) >= alpha I / E (Eq. 9).
+ *
+ * Where Algorithm 1 is silent: loads are computed before the first evaluation; expert e belongs to
+ * device e / (E/D); the heaviest device (ties: lowest index) contributes its unselected expert with
+ * the most inputs (ties: lowest id) and the search stops when it has none left (the paper's
+ * "i in Used" when E = D); the n devices that are skipped are the non-owners with the fewest inputs
+ * of the expert (ties: lowest index); times are IEEE doubles, a new placement is kept only if its
+ * time is strictly smaller.
+ */
+typedef struct {
+    int D, E;                   /* devices, experts; 1 <= D <= 64, E <= 1024, E % D == 0 */
+    int n;                      /* devices a selected expert is not transferred to, 0 <= n <= D-1 */
+    int overlap;                /* 0: Eq. 7;  1: Eq. 8 */
+    double alpha;               /* coefficient of the balance test, Eq. 9 */
+    double size_input;          /* bytes of one input */
+    double size_params;         /* bytes of one expert's parameters */
+    double size_grads;          /* bytes of one expert's gradients */
+    double B;                   /* average communication bandwidth, bytes/s, > 0 */
+    double t;                   /* computation throughput, inputs/s, > 0 */
+    double T_FNEC, T_BNEC;      /* forward/backward time of the non-MoE layer, s (Eq. 8 only) */
+} moe_planner_t;
+
+/* Outputs of moe_plan (all device memory, all written by every call):
+ *   expert_dest[D][E] : row j is device j's plan in the form moe_dispatch takes: j where device j
+ *                       holds the expert (owner or replica), the owner elsewhere
+ *   selected[E]       : experts in the order the search selected them, -1 after the last
+ *   skipped[E]        : bit j of entry r is set when device j does not receive the r-th selected expert
+ *   H[D], R[D]        : inputs computed / received per device under the returned placement
+ *   times[2 + E]      : T' without a placement, T' of the returned placement, T' after each selection
+ *   info[2]           : cnt (selections kept in the placement), s (selections made by the search) */
+typedef struct {
+    int32_t* expert_dest;
+    int32_t* selected;
+    uint64_t* skipped;
+    int64_t* H;
+    int64_t* R;
+    double* times;
+    int32_t* info;
+} moe_plan_out_t;
+
+/* in: cfg (host), gating[D][E] int32 (device): inputs on device i routed to expert e, each >= 0
+ * out: see moe_plan_out_t (struct on the host, pointers to device memory).
+ * Errors: MOE_ERR_NULL, MOE_ERR_SHAPE (sizes, n, non-positive or non-finite model constants). */
+int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,7 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
+    "moe_plan",
 ]
 
 
@@ -40,6 +41,15 @@ class _Shape(ctypes.Structure):
 class _Layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in
                 ("slot_of_expert", "slot_offsets", "dest_offsets", "dest_slots", "pos", "perm")]
+
+
+class _Planner(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("D", "E", "n", "overlap")] + \
+               [(n, ctypes.c_double) for n in ("alpha", "size_input", "size_params", "size_grads", "B", "t", "T_FNEC", "T_BNEC")]
+
+
+class _PlanOut(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("expert_dest", "selected", "skipped", "H", "R", "times", "info")]
 
 
 _lib = None
@@ -68,6 +78,7 @@ def load() -> ctypes.CDLL:
         lib.moe_expert_ffn_bwd.argtypes = [vp] * 5 + [ctypes.POINTER(_Layout)] + [vp] * 9
         lib.moe_dispatch_bwd.argtypes = [vp] * 5
         lib.moe_gate_bwd.argtypes = [vp] * 6
+        lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
     return _lib
 
@@ -86,6 +97,35 @@ def _ptr(t: Optional[torch.Tensor], dtype: torch.dtype, numel: int, name: str) -
 
 def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
+
+
+class PlanBuffers:
+    """Device arrays moe_plan writes (see moe_plan_out_t)."""
+
+    def __init__(self, D: int, E: int, device="cuda:0"):
+        self.D, self.E = D, E
+        self.expert_dest = torch.zeros(D, E, dtype=torch.int32, device=device)
+        self.selected = torch.zeros(E, dtype=torch.int32, device=device)
+        self.skipped = torch.zeros(E, dtype=torch.int64, device=device)      # bit masks, read as unsigned
+        self.H = torch.zeros(D, dtype=torch.int64, device=device)
+        self.R = torch.zeros(D, dtype=torch.int64, device=device)
+        self.times = torch.zeros(2 + E, dtype=torch.float64, device=device)
+        self.info = torch.zeros(2, dtype=torch.int32, device=device)
+        self.c = _PlanOut(*(t.data_ptr() for t in (self.expert_dest, self.selected, self.skipped, self.H, self.R,
+                                                   self.times, self.info)))
+
+
+def plan(gating: torch.Tensor, out: PlanBuffers, *, n: int, overlap: bool, alpha: float, size_input: float,
+         size_params: float, size_grads: float, B: float, t: float, T_FNEC: float = 0.0, T_BNEC: float = 0.0) -> None:
+    """moe_plan: greedy search for a lightweight expert placement on the device (argument marshalling only)."""
+    lib = load()
+    D, E = out.D, out.E
+    g = _ptr(gating, torch.int32, D * E, "gating")
+    cfg = _Planner(D, E, int(n), int(bool(overlap)), float(alpha), float(size_input), float(size_params),
+                   float(size_grads), float(B), float(t), float(T_FNEC), float(T_BNEC))
+    rc = lib.moe_plan(ctypes.byref(cfg), g, ctypes.byref(out.c), _stream())
+    if rc != 0:
+        raise MoeError(rc, "moe_plan", lib.moe_status_string(rc).decode())
 
 
 class Layout:

@@ -2,6 +2,8 @@
 // Nothing here synchronises or allocates device memory (moe_read_status excepted).
 #include "internal.h"
 
+#include <cmath>
+
 #include <new>
 
 namespace {
@@ -216,6 +218,19 @@ int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int
 {
     if (!h || !dw || !logits || !idx || !dlogits) return MOE_ERR_NULL;
     return hip_status(launch_gate_bwd(h->s, dw, logits, idx, dlogits, (hipStream_t)stream));
+}
+
+int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream)
+{
+    if (!cfg || !gating || !out) return MOE_ERR_NULL;
+    if (!out->expert_dest || !out->selected || !out->skipped || !out->H || !out->R || !out->times || !out->info) return MOE_ERR_NULL;
+    const moe_planner_t& c = *cfg;
+    if (c.D < 1 || c.D > 64 || c.E < c.D || c.E > 1024 || c.E % c.D != 0) return MOE_ERR_SHAPE;
+    if (c.n < 0 || c.n > c.D - 1 || (c.overlap != 0 && c.overlap != 1)) return MOE_ERR_SHAPE;
+    const double pos[] = {c.B, c.t}, nonneg[] = {c.alpha, c.size_input, c.size_params, c.size_grads, c.T_FNEC, c.T_BNEC};
+    for (double v : pos) if (!(v > 0.0) || !std::isfinite(v)) return MOE_ERR_SHAPE;
+    for (double v : nonneg) if (!(v >= 0.0) || !std::isfinite(v)) return MOE_ERR_SHAPE;
+    return hip_status(launch_plan(c, gating, *out, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -43,6 +43,7 @@ hipError_t launch_scatter_rows(const moe_shape_t& s, const void* X, const int32_
 hipError_t launch_combine(const moe_shape_t& s, const void* Yp, const int32_t* pos, const float* w, void* out, hipStream_t st);
 hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void* Yp, const int32_t* pos,
                               const float* w, void* dYp, float* dw, hipStream_t st);
+hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
 hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
 
 struct ffn_args {

@@ -208,3 +208,31 @@ def group_of_expert(expert_dest: np.ndarray, self_dest: int = 0) -> np.ndarray:
 def balance_degree(counts: Sequence[int]) -> float:
     """Standard deviation of the input distribution (Section 6.3, balance capability)."""
     return float(np.std(np.asarray(counts, dtype=np.float64)))
+
+
+def make_gating(cfg: MoEConfig, counts_self: Sequence[int], iteration: int = 0, base_seed: Optional[int] = None) -> np.ndarray:
+    """The P x E matrix of routing counts the planner consumes (Algorithm 1's `gating`): row
+    `self_dest` is this GPU's realised histogram, every other row is a multinomial draw of the same
+    number of assignments from the realised shares (devices see the same skewed distribution,
+    Section 3).  Only random numbers are drawn here."""
+    counts_self = np.asarray(counts_self, dtype=np.int64)
+    seed = (seed_for(cfg.index, iteration) if base_seed is None else base_seed) + 500
+    rng = np.random.default_rng(seed)
+    A = int(counts_self.sum())
+    p = counts_self.astype(np.float64) / max(A, 1)
+    g = np.empty((cfg.P, cfg.E), dtype=np.int32)
+    for j in range(cfg.P):
+        g[j] = counts_self if j == cfg.self_dest else rng.multinomial(A, p)
+    return g
+
+
+def planner_constants(cfg: MoEConfig) -> dict:
+    """Constants of the planner's performance model for one configuration (Table 2 of the paper):
+    bytes per input / per expert from the shapes, an xGMI-class link bandwidth and an expert
+    throughput of the order this library reaches.  Inputs of the harness, not measurements."""
+    elt = 4 if cfg.dtype == "f32" else 2
+    flops_per_input = 2.0 * cfg.n_mats * cfg.d * cfg.h
+    return dict(size_input=float(cfg.d * elt), size_params=float(cfg.n_mats * cfg.d * cfg.h * elt),
+                size_grads=float(cfg.n_mats * cfg.d * cfg.h * 4), B=150e9, t=1.0e15 / flops_per_input,
+                T_FNEC=0.0, T_BNEC=0.0)
+

@@ -61,3 +61,26 @@ def test_create_validates_shapes(lib):
     assert create(T=0) == -2
     assert lib.moe_create(None, None) == -1
     assert lib.moe_status_string(-3).decode() == "expert placement out of range"
+
+
+def test_plan_validates_arguments(lib):
+    """moe_plan checks its arguments on the host before anything is launched (no GPU needed here)."""
+    from paper_2411_10003_amd.binding import _PlanOut, _Planner
+    good = dict(D=4, E=8, n=1, overlap=0, alpha=1.0, size_input=8.0, size_params=16.0, size_grads=16.0, B=1.0, t=1.0,
+                T_FNEC=0.0, T_BNEC=0.0)
+    out = _PlanOut(*([0x1000] * 7))                       # never dereferenced: every call below fails validation
+
+    def call(**kw):
+        f = dict(good)
+        f.update(kw)
+        c = _Planner(*(f[n] for n, _ in _Planner._fields_))
+        return lib.moe_plan(ctypes.byref(c), ctypes.c_void_p(0x1000), ctypes.byref(out), None)
+
+    assert lib.moe_plan(None, None, None, None) == -1
+    assert call(D=0) == -2 and call(D=65, E=65) == -2 and call(E=6) == -2 and call(E=2048, D=64) == -2
+    assert call(n=-1) == -2 and call(n=4) == -2 and call(overlap=2) == -2
+    assert call(B=0.0) == -2 and call(t=-1.0) == -2 and call(alpha=float("nan")) == -2 and call(size_params=float("inf")) == -2
+    missing = _PlanOut(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    c = _Planner(*(good[n] for n, _ in _Planner._fields_))
+    assert lib.moe_plan(ctypes.byref(c), ctypes.c_void_p(0x1000), ctypes.byref(missing), None) == -1
+

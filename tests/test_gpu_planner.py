@@ -1,0 +1,117 @@
+"""GPU parity of moe_plan (greedy placement search on the device) against the planner oracle.
+
+Everything the search decides is an integer, and the two estimated times it compares are IEEE doubles
+evaluated in the same order on both sides, so every output is compared exactly.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as G
+from oracle import planner_oracle as po
+from paper_2411_10003_amd import binding, workload as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def run_plan(g, n, m):
+    D, E = g.shape
+    out = binding.PlanBuffers(D, E)
+    binding.plan(G.dev(g.astype(np.int32)), out, n=n, overlap=m.overlap, alpha=m.alpha, size_input=m.size_input,
+                 size_params=m.size_params, size_grads=m.size_grads, B=m.B, t=m.t, T_FNEC=m.T_FNEC, T_BNEC=m.T_BNEC)
+    torch.cuda.synchronize()
+    return out
+
+
+def check(g, n, m):
+    D, E = g.shape
+    out = run_plan(g, n, m)
+    r = po.greedy_search(g, n, m)
+    cnt, s = (int(v) for v in G.host(out.info))
+    assert cnt == r["cnt"] and s == len(r["L"])
+    sel = G.host(out.selected)
+    assert sel[:s].tolist() == r["L"] and (sel[s:] == -1).all()
+    masks = G.host(out.skipped).astype(np.uint64)
+    for rank, nb in enumerate(r["n_bottoms"]):
+        assert [j for j in range(D) if (int(masks[rank]) >> j) & 1] == nb
+    assert (masks[s:] == 0).all()
+    times = G.host(out.times)
+    assert times[0] == r["T_base"] and times[1] == r["T_output"]
+    assert times[2:2 + s].tolist() == [t["T"] for t in r["trace"]]         # bit-exact doubles
+    assert G.host(out.H).tolist() == r["H"].tolist() and G.host(out.R).tolist() == r["R"].tolist()
+    assert np.array_equal(G.host(out.expert_dest), r["expert_dest"])
+    return out, r
+
+
+def model(**kw):
+    base = dict(size_input=1.0, size_params=2.0, size_grads=2.0, B=1.0, t=1.0, alpha=0.2)
+    base.update(kw)
+    return po.PlannerModel(**base)
+
+
+GATING4 = np.array([[6, 1, 1, 0], [5, 2, 0, 1], [4, 0, 3, 1], [1, 1, 0, 6]], dtype=np.int64)
+
+
+def test_hand_traced_example():
+    """The example traced by hand in the oracle's pins (Algorithm 1, Eq. 7 and Eq. 8)."""
+    out, r = check(GATING4, 1, model())
+    assert G.host(out.selected)[:4].tolist() == [0, 1, 3, 2] and int(G.host(out.info)[0]) == 1
+    assert G.host(out.times)[:6].tolist() == [88.0, 38.0, 38.0, 41.0, 40.0, 43.0]
+    out, r = check(GATING4, 1, model(overlap=True, T_FNEC=1.0, T_BNEC=1.0))
+    assert int(G.host(out.info)[0]) == 3 and G.host(out.times)[1] == 31.0
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_count_matrices(seed):
+    rng = np.random.default_rng(7000 + seed)
+    D = int(rng.choice([1, 2, 3, 4, 8, 16, 33, 64]))
+    E = D * int(rng.choice([1, 2, 4, 16]))
+    E = min(E, 1024 // D * D)
+    p = rng.dirichlet(np.full(E, float(rng.choice([0.05, 0.3, 3.0]))))
+    g = rng.multinomial(int(rng.choice([0, 7, 1000, 65536, 2_000_000_000])), p, size=D).astype(np.int64)
+    n = int(rng.integers(0, D))
+    m = model(size_input=float(rng.choice([1.0, 4096.0, 8192.0])), size_params=float(rng.choice([2.0, 5e4, 3.5e8])),
+              size_grads=float(rng.choice([2.0, 5e4, 7e8])), B=float(rng.choice([1.0, 1e3, 1.5e11])),
+              t=float(rng.choice([1.0, 10.0, 2.8e6])), alpha=float(rng.choice([0.0, 0.1, 0.5, 1.0])),
+              overlap=bool(seed % 2), T_FNEC=float(rng.choice([0.0, 1e-3])), T_BNEC=float(rng.choice([0.0, 2e-3])))
+    check(g, n, m)
+
+
+@pytest.mark.parametrize("index", [1, 2, 3, 4])
+@pytest.mark.parametrize("overlap", [False, True])
+def test_config_shaped_count_matrices(index, overlap):
+    """Count matrices with the skew of the configurations (row `self` is the realised routing histogram)."""
+    cfg = wl.CONFIGS[index]
+    small = wl.scaled(cfg, T=2048, d=64, h=64)                 # routing only: the histogram has the configuration's skew
+    case = G.Case(small)
+    g = wl.make_gating(small, case.route["counts"]).astype(np.int64)
+    consts = wl.planner_constants(cfg)
+    for n in sorted({0, 1, cfg.P // 2, cfg.P - 1}):
+        out, r = check(g, n, po.PlannerModel(alpha=1.0, overlap=overlap, **consts))
+        assert r["T_output"] <= r["T_base"]
+
+
+def test_degenerate_inputs():
+    z = np.zeros((4, 8), dtype=np.int64)
+    check(z, 1, model())                                        # nothing routed anywhere
+    one = z.copy(); one[:, 5] = 1000
+    check(one, 0, model())                                      # everything to one expert
+    check(one, 3, model())
+    check(np.full((8, 8), 100, dtype=np.int64), 2, model(alpha=1.0))   # balanced from the start: no selection
+    check(np.array([[3, 9, 1, 0]], dtype=np.int64), 0, model())        # one device
+
+
+def test_plan_row_feeds_dispatch():
+    """Row `self` of expert_dest is handed to moe_dispatch as it lies in device memory."""
+    cfg = wl.scaled(wl.CONFIGS[1], T=1024, d=128, h=128)
+    case0 = G.Case(cfg)
+    g = wl.make_gating(cfg, case0.route["counts"]).astype(np.int64)
+    m = po.PlannerModel(alpha=1.0, overlap=False, **wl.planner_constants(wl.CONFIGS[1]))
+    out, r = check(g, 1, m)
+    case = G.Case(cfg, expert_dest=r["expert_dest"][cfg.self_dest])
+    hd = G.make_handle(cfg, G=cfg.E)
+    b = binding.LayerBuffers(hd, False)
+    hd.dispatch(out.expert_dest[cfg.self_dest], case.dX, G.dev(case.route["idx"]), G.dev(case.route["counts"]), b.layout, b.Xp)
+    assert hd.read_status() == 0
+    G.assert_layout_equal(b, case.lay)
+    assert np.array_equal(G.host(b.Xp), G.orc.dispatch(case.inp["X"], case.lay["perm"], cfg.k))
