@@ -119,7 +119,9 @@ int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void*
  * device are computed locally, the others go to the expert's owner; Fig. 2: first all-to-all).
  *   in : expert_dest[E] int32 in [0,P): destination that computes this GPU's inputs of expert e
  *        (== self for owned and replicated experts); X[T,d] elt; idx[A]; counts[E] as returned by
- *        moe_expert_counts for the same idx
+ *        moe_expert_counts for the same idx.  If the call of this handle before this one that used
+ *        the routing part of the workspace was a moe_expert_counts of this idx pointer, its per-chunk
+ *        histograms are reused (once): idx must not have been rewritten in between
  *   out: every array of *layout (host struct of device pointers); Xp[A,d] elt with
  *        Xp[r,:] = X[perm[r] / k, :] (bit copies) */
 int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,

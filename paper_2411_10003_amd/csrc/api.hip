@@ -136,6 +136,8 @@ int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void*
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
     if (e == hipSuccess) e = launch_counts_from_hist(h->s, c.chunk_hist(), h->n_chunks, counts, st);
+    h->hist_idx = (e == hipSuccess) ? idx : nullptr;
+    h->hist_ws = ws;
     return hip_status(e);
 }
 
@@ -148,10 +150,17 @@ int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, cons
     if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
     const Carve c{(char*)ws, h};
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
-    if (e == hipSuccess)
-        e = launch_layout_scan(h->s, expert_dest, counts, c.chunk_hist(), c.chunk_base(), h->n_chunks, *L, c.status(), st);
-    if (e == hipSuccess) e = launch_positions(h->s, idx, c.chunk_base(), h->n_chunks, *L, st);
+    // the per-chunk histograms of moe_expert_counts are still in the workspace when that call counted this idx
+    hipError_t e = hipSuccess;
+    if (h->hist_idx != idx || h->hist_ws != ws) e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
+    h->hist_idx = nullptr;                                // good for one dispatch
+    if (e == hipSuccess && layout_positions_fusable(h->s, h->n_chunks)) {
+        e = launch_layout_positions(h->s, idx, expert_dest, counts, c.chunk_hist(), h->n_chunks, *L, c.status(), st);
+    } else {
+        if (e == hipSuccess)
+            e = launch_layout_scan(h->s, expert_dest, counts, c.chunk_hist(), c.chunk_base(), h->n_chunks, *L, c.status(), st);
+        if (e == hipSuccess) e = launch_positions(h->s, idx, c.chunk_base(), h->n_chunks, *L, st);
+    }
     if (e == hipSuccess) e = launch_scatter_rows(h->s, X, L->pos, Xp, st);
     return hip_status(e);
 }

@@ -18,6 +18,9 @@ struct moe_ctx {
     size_t off_du;         // elt [A,h]  dU (SwiGLU)
     size_t ws_bytes;
     int n_chunks;          // ceil(A / ROUTE_CHUNK)
+    // per-chunk histograms left in a workspace by the last moe_expert_counts: whose they are
+    const void* hist_idx = nullptr;
+    const void* hist_ws = nullptr;
 };
 
 // Assignments handled by one wave of the routing kernels.
@@ -43,6 +46,9 @@ hipError_t launch_scatter_rows(const moe_shape_t& s, const void* X, const int32_
 hipError_t launch_combine(const moe_shape_t& s, const void* Yp, const int32_t* pos, const float* w, void* out, hipStream_t st);
 hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void* Yp, const int32_t* pos,
                               const float* w, void* dYp, float* dw, hipStream_t st);
+bool layout_positions_fusable(const moe_shape_t& s, int n_chunks);
+hipError_t launch_layout_positions(const moe_shape_t& s, const int32_t* idx, const int32_t* expert_dest, const int32_t* counts,
+                                   const int32_t* chunk_hist, int n_chunks, const moe_layout_t& L, int32_t* status, hipStream_t st);
 hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
 hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
 

@@ -160,6 +160,116 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void positions_kernel(
     }
 }
 
+// Layout and positions in one launch, for the common case of few chunks: every block rebuilds the
+// (small) layout from the counts and the placement in LDS, block 0 publishes it, and every wave gets
+// the base of its chunk by summing the histograms of the chunks before it instead of reading a
+// prefix table that a separate single-block launch would have to write first.
+constexpr int FUSED_MAX_E = 64, FUSED_MAX_CHUNKS = 1024;
+
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void layout_positions_kernel(
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ expert_dest, const int32_t* __restrict__ counts,
+    const int32_t* __restrict__ chunk_hist,
+    int32_t* __restrict__ slot_of_expert, int32_t* __restrict__ slot_offsets,
+    int32_t* __restrict__ dest_offsets, int32_t* __restrict__ dest_slots, int32_t* __restrict__ status,
+    int32_t* __restrict__ pos, int32_t* __restrict__ perm, int A, int E, int P, int self, int Gcap, int n_chunks)
+{
+    __shared__ int32_t dest[FUSED_MAX_E], slot_of[FUSED_MAX_E], slot_cnt[FUSED_MAX_E], slot_off[FUSED_MAX_E + 1];
+    __shared__ int32_t next_all[ROUTE_WAVES][FUSED_MAX_E];
+    __shared__ int32_t flag;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) flag = 0;
+    __syncthreads();
+    if (tid < E) {
+        int p = expert_dest[tid];
+        if (p < 0 || p >= P) { atomicOr(&flag, 1); p = p < 0 ? 0 : P - 1; }
+        dest[tid] = p;
+    }
+    __syncthreads();
+    if (tid < E) {                                          // slot = rank by (destination, id)
+        const int p = dest[tid];
+        int sl = 0;
+        for (int f = 0; f < E; ++f) sl += (dest[f] < p) || (dest[f] == p && f < tid);
+        slot_of[tid] = sl;
+        slot_cnt[sl] = counts[tid];
+    }
+    __syncthreads();
+    if (wave == 0) {                                        // exclusive scan of the slot counts (E <= 64: one wave)
+        const int v = lane < E ? slot_cnt[lane] : 0;
+        int incl = v;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        if (lane < E) slot_off[lane] = incl - v;
+        if (lane == 63) slot_off[E] = incl;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {                                  // one block publishes the layout
+        if (tid < E) slot_of_expert[tid] = slot_of[tid];
+        if (tid <= E) slot_offsets[tid] = slot_off[tid];
+        if (tid <= P) {
+            int first = 0;
+            for (int f = 0; f < E; ++f) first += (dest[f] < tid);
+            dest_slots[tid] = first;
+            dest_offsets[tid] = slot_off[first];
+        }
+        if (tid == 0) {
+            int hosted = 0;
+            for (int e = 0; e < E; ++e) hosted += (dest[e] == self);
+            *status = (flag || hosted > Gcap) ? (int32_t)MOE_ERR_PLAN : (int32_t)MOE_OK;
+        }
+    }
+    const int chunk = blockIdx.x * ROUTE_WAVES + wave;
+    if (chunk >= n_chunks) return;
+    volatile int32_t* next = next_all[wave];
+    {   // rows of every expert in the chunks before this one.  The histograms of those chunks are one
+        // flat array of 16-byte pieces, q = E/4 per chunk; q divides 64, so a lane striding by 64 always
+        // meets the same four experts and all of its loads are independent.
+        const int q = E >> 2;
+        const int4* hp = reinterpret_cast<const int4*>(chunk_hist);
+        const int n4 = chunk * q;
+        int4 acc = make_int4(0, 0, 0, 0);
+#pragma unroll 4
+        for (int i = lane; i < n4; i += 64) {
+            const int4 v = hp[i];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        for (int off = q; off < 64; off <<= 1) {
+            acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
+            acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
+        }
+        if (lane < q) {
+            const int e = 4 * lane;
+            next[e + 0] = slot_off[slot_of[e + 0]] + acc.x;
+            next[e + 1] = slot_off[slot_of[e + 1]] + acc.y;
+            next[e + 2] = slot_off[slot_of[e + 2]] + acc.z;
+            next[e + 3] = slot_off[slot_of[e + 3]] + acc.w;
+        }
+    }
+    for (int r = 0; r < ROUTE_CHUNK / 64; ++r) {
+        const int a = chunk * ROUTE_CHUNK + r * 64 + lane;
+        int e = -1;
+        if (a < A) {
+            e = idx[a];
+            if (e < 0 || e >= E) e = -1;
+        }
+        unsigned long long active = __ballot(e >= 0);
+        while (active) {
+            const int leader = __ffsll((long long)active) - 1;
+            const int e0 = __shfl(e, leader, 64);
+            const unsigned long long m = __ballot(e == e0);
+            const int base = next[e0];
+            if (e == e0) {
+                const int row = base + __popcll(m & lanemask_lt(lane));
+                pos[a] = row;
+                perm[row] = a;
+            }
+            if (lane == leader) next[e0] = base + __popcll(m);
+            active &= ~m;
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_chunk_hist(const moe_shape_t& s, const int32_t* idx, int32_t* chunk_hist, int n_chunks, hipStream_t st)
@@ -199,3 +309,20 @@ hipError_t launch_positions(const moe_shape_t& s, const int32_t* idx, const int3
                        idx, chunk_base, L.slot_of_expert, L.slot_offsets, L.pos, L.perm, s.T * s.k, s.E, n_chunks);
     return hipGetLastError();
 }
+
+bool layout_positions_fusable(const moe_shape_t& s, int n_chunks)
+{
+    const bool e_ok = s.E >= 4 && s.E <= FUSED_MAX_E && (s.E & (s.E - 1)) == 0;      // a power of two: E/4 divides 64
+    return e_ok && s.P <= ROUTE_WAVES * 64 - 1 && n_chunks >= 1 && n_chunks <= FUSED_MAX_CHUNKS;
+}
+
+hipError_t launch_layout_positions(const moe_shape_t& s, const int32_t* idx, const int32_t* expert_dest, const int32_t* counts,
+                                   const int32_t* chunk_hist, int n_chunks, const moe_layout_t& L, int32_t* status, hipStream_t st)
+{
+    const int grid = (n_chunks + ROUTE_WAVES - 1) / ROUTE_WAVES;
+    hipLaunchKernelGGL(layout_positions_kernel, dim3(grid), dim3(ROUTE_WAVES * 64), 0, st, idx, expert_dest, counts, chunk_hist,
+                       L.slot_of_expert, L.slot_offsets, L.dest_offsets, L.dest_slots, status, L.pos, L.perm,
+                       s.T * s.k, s.E, s.P, s.self, s.G, n_chunks);
+    return hipGetLastError();
+}
+
