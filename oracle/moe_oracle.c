@@ -406,3 +406,41 @@ void orc_gate_bwd(const double* dw, const float* logits, const int32_t* idx, int
         free(p);
     }
 }
+
+/* ---------------------------------------------------------------------------------------
+ * Backward of the gate's linear map logit[t,e] = b[e] + sum_c X[t,c] Wg[c,e] (the gate network of
+ * Section 2.1), given dlogits:
+ *   dWg[c,e] = sum_t X[t,c] dlogits[t,e],   dbg[e] = sum_t dlogits[t,e]
+ */
+void orc_gate_bwd_params(const float* X, const double* dlogits, int T, int d, int E, double* dWg, double* dbg)
+{
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < d; ++c)
+        for (int e = 0; e < E; ++e) {
+            double s = 0.0;
+            for (int t = 0; t < T; ++t) s += (double)X[(size_t)t * d + c] * dlogits[(size_t)t * E + e];
+            dWg[(size_t)c * E + e] = s;
+        }
+    for (int e = 0; e < E; ++e) {
+        double s = 0.0;
+        for (int t = 0; t < T; ++t) s += dlogits[(size_t)t * E + e];
+        dbg[e] = s;
+    }
+}
+
+/* Gradient of the layer input: the expert path (the backward of the send, see orc_dispatch_bwd) plus
+ * the gate path dlogits Wg^T:  dX[t,c] = sum_j dXp[pos[t*k+j],c] + sum_e dlogits[t,e] Wg[c,e]. */
+void orc_input_grad(const double* dXp, const int32_t* pos, const double* dlogits, const float* Wg,
+                    int T, int d, int E, int k, double* dX)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        for (int c = 0; c < d; ++c) {
+            double s = 0.0;
+            for (int j = 0; j < k; ++j) s += dXp[(size_t)pos[(size_t)t * k + j] * d + c];
+            double g = 0.0;
+            for (int e = 0; e < E; ++e) g += dlogits[(size_t)t * E + e] * (double)Wg[(size_t)c * E + e];
+            dX[(size_t)t * d + c] = s + g;
+        }
+}
+

@@ -220,6 +220,27 @@ def gate_bwd(dw, logits, idx, renorm: int) -> np.ndarray:
     return out
 
 
+def gate_bwd_params(X, dlogits):
+    """dWg[d,E], dbg[E] of the gate's linear map."""
+    X, dlogits = _f32(X), _f64(dlogits)
+    T, d = X.shape
+    E = dlogits.shape[1]
+    dWg = np.empty((d, E), dtype=np.float64)
+    dbg = np.empty(E, dtype=np.float64)
+    lib().orc_gate_bwd_params(_p(X), _p(dlogits), T, d, E, _p(dWg), _p(dbg))
+    return dWg, dbg
+
+
+def input_grad(dXp, pos, dlogits, Wg, k: int) -> np.ndarray:
+    """Expert-path plus gate-path gradient of the layer input."""
+    dXp, pos, dlogits, Wg = _f64(dXp), _i32(pos), _f64(dlogits), _f32(Wg)
+    d, E = Wg.shape
+    T = pos.size // k
+    dX = np.empty((T, d), dtype=np.float64)
+    lib().orc_input_grad(_p(dXp), _p(pos), _p(dlogits), _p(Wg), T, d, E, k, _p(dX))
+    return dX
+
+
 # ------------------------------------------------------------------------------------------
 # The layer in call order (routing part is cheap and always complete; the FFN part is
 # evaluated for the assignments asked for).

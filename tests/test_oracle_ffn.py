@@ -250,3 +250,46 @@ def test_gate_bwd_vs_finite_differences(orc, k, renorm, E):
             lm[t, e] -= np.float32(eps)
             num = ((wsel(lp) - wsel(lm)) * dw).sum() / (2 * eps)
             assert abs(num - dl[t, e]) <= 1e-5 * max(1.0, np.abs(dl).max()), (t, e)
+
+
+def test_gate_linear_backward_vs_matmul_and_finite_differences(orc):
+    """The gate is linear in Wg, b and X (Section 2.1), so its backward is two matrix products: checked
+    against numpy's, and against central differences of <logits, dlogits> with exactly representable steps."""
+    rng = np.random.default_rng(77)
+    T, d, E, k = 9, 12, 5, 2
+    X = _grid(rng.standard_normal((T, d)))
+    Wg = _grid(rng.standard_normal((d, E)) * 0.5)
+    bg = _grid(rng.standard_normal(E))
+    dl = rng.standard_normal((T, E))
+    dWg, dbg = orc.gate_bwd_params(X, dl)
+    assert np.allclose(dWg, X.astype(np.float64).T @ dl, rtol=1e-13, atol=1e-13)
+    assert np.allclose(dbg, dl.sum(axis=0), rtol=1e-13, atol=1e-13)
+    assert dWg.shape == (d, E) and not np.allclose(dWg, (X.astype(np.float64).T @ dl).T.reshape(d, E))   # not the transpose
+
+    def inner(Xv, Wv, bv):                                   # <logits, dlogits> in double from the definition
+        return float(((Xv.astype(np.float64) @ Wv.astype(np.float64) + bv.astype(np.float64)) * dl).sum())
+
+    eps = np.float32(2.0 ** -6)
+    for (c, e) in [(0, 0), (3, 4), (11, 2)]:
+        Wp, Wm = Wg.copy(), Wg.copy()
+        Wp[c, e] += eps; Wm[c, e] -= eps
+        assert abs((inner(X, Wp, bg) - inner(X, Wm, bg)) / (2 * float(eps)) - dWg[c, e]) < 1e-9
+    for e in range(E):
+        bp, bm = bg.copy(), bg.copy()
+        bp[e] += eps; bm[e] -= eps
+        assert abs((inner(X, Wg, bp) - inner(X, Wg, bm)) / (2 * float(eps)) - dbg[e]) < 1e-9
+
+    # input gradient = expert path (sum of the k returned rows) + gate path dlogits Wg^T
+    A = T * k
+    pos = rng.permutation(A).astype(np.int32)
+    dXp = rng.standard_normal((A, d))
+    dX = orc.input_grad(dXp, pos, dl, Wg, k)
+    assert np.allclose(dX, orc.dispatch_bwd(dXp, pos, k) + dl @ Wg.astype(np.float64).T, rtol=1e-13, atol=1e-13)
+    for (t, c) in [(0, 0), (4, 7), (8, 11)]:
+        Xp_, Xm_ = X.copy(), X.copy()
+        Xp_[t, c] += eps; Xm_[t, c] -= eps
+        gate_path = (inner(Xp_, Wg, bg) - inner(Xm_, Wg, bg)) / (2 * float(eps))
+        expert_path = sum(dXp[pos[t * k + j], c] for j in range(k))
+        assert abs(gate_path + expert_path - dX[t, c]) < 1e-9
+    # with dlogits = 0 the gate path vanishes and the result is the plain backward of the send
+    assert np.array_equal(orc.input_grad(dXp, pos, np.zeros((T, E)), Wg, k), orc.dispatch_bwd(dXp, pos, k))
