@@ -243,6 +243,27 @@ def main():
         per_call["plan"]["oracle_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
         assert ref["cnt"] == int(info[0]) and ref["T_output"] == float(ptimes[1]), "planner disagrees with its oracle"
 
+    # the rest of the gate's backward (parameter gradients, gate path of the input gradient): beside the step
+    if cfg.backward and E <= 64:
+        dWg = torch.empty(d, E, dtype=torch.float32, device=dev)
+        dbg = torch.empty(E, dtype=torch.float32, device=dev)
+        extra = {
+            "gate_bwd_params": (lambda: hd.gate_bwd_params(X, b.dlogits, dWg, dbg), T * d * es + T * E * 4),
+            "input_grad": (lambda: hd.input_grad(b.dXp, b.layout.pos, b.dlogits, Wg, b.dX), (1 + k) * T * d * es + T * E * 4),
+        }
+        for name, (fn, nbytes) in extra.items():
+            fn()
+            torch.cuda.synchronize()
+            ee = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ee[0].record()
+            for _ in range(10):
+                fn()
+            ee[1].record()
+            torch.cuda.synchronize()
+            ms = ee[0].elapsed_time(ee[1]) / 10
+            per_call[name] = {"ms": round(ms, 4), "in_step": False, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                              "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
     result = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,

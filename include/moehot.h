@@ -170,6 +170,19 @@ int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* 
 int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int32_t* idx,
                  float* dlogits, void* stream);
 
+/* Gradients of the gate's parameters (the gate network of Section 2.1 is the linear map
+ * logit[t,e] = bg[e] + sum_c X[t,c] Wg[c,e]):  dWg[c,e] = sum_t X[t,c] dlogits[t,e],  dbg[e] = sum_t dlogits[t,e].
+ * fp32 sums in a fixed order (same bits every run).  E <= 64 (else MOE_ERR_UNIMPLEMENTED).  Uses the workspace.
+ *   in : X[T,d] elt, dlogits[T,E] float;  out: dWg[d,E] float, dbg[E] float */
+int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, float* dWg, float* dbg,
+                        void* ws, void* stream);
+
+/* Complete gradient of the layer input: the backward of the send (as moe_dispatch_bwd) plus the gate
+ * path, rounded once:  dX[t,:] = sum_j dXp[pos[t*k+j],:] + sum_e dlogits[t,e] Wg[:,e].  E <= 64.
+ *   in : dXp[A,d] elt, pos[A], dlogits[T,E] float, Wg[d,E] float;  out: dX[T,d] elt */
+int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const float* dlogits, const float* Wg,
+                   void* dX, void* stream);
+
 /* ---- planner (Sections 4.2-4.3 and 5.3 of the paper) ------------------------------------------
  *
  * moe_plan runs the paper's greedy search for a lightweight expert placement (Algorithm 1) on the

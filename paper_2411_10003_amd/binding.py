@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
-    "moe_plan",
+    "moe_plan", "moe_gate_bwd_params", "moe_input_grad",
 ]
 
 
@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
         lib.moe_expert_ffn_bwd.argtypes = [vp] * 5 + [ctypes.POINTER(_Layout)] + [vp] * 9
         lib.moe_dispatch_bwd.argtypes = [vp] * 5
         lib.moe_gate_bwd.argtypes = [vp] * 6
+        lib.moe_gate_bwd_params.argtypes = [vp] * 7
+        lib.moe_input_grad.argtypes = [vp] * 7
         lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
     return _lib
@@ -251,6 +253,20 @@ class Handle:
         self._check(self.lib.moe_gate_bwd(
             self._h, _ptr(dw, f32, self.A, "dw"), _ptr(logits, f32, self.T * self.E, "logits"),
             _ptr(idx, torch.int32, self.A, "idx"), _ptr(dlogits, f32, self.T * self.E, "dlogits"), _stream()), "moe_gate_bwd")
+
+    def gate_bwd_params(self, X, dlogits, dWg, dbg):
+        f32 = torch.float32
+        self._check(self.lib.moe_gate_bwd_params(
+            self._h, _ptr(X, self.elt, self.T * self.d, "X"), _ptr(dlogits, f32, self.T * self.E, "dlogits"),
+            _ptr(dWg, f32, self.d * self.E, "dWg"), _ptr(dbg, f32, self.E, "dbg"), self._ws(), _stream()),
+            "moe_gate_bwd_params")
+
+    def input_grad(self, dXp, pos, dlogits, Wg, dX):
+        f32 = torch.float32
+        self._check(self.lib.moe_input_grad(
+            self._h, _ptr(dXp, self.elt, self.A * self.d, "dXp"), _ptr(pos, torch.int32, self.A, "pos"),
+            _ptr(dlogits, f32, self.T * self.E, "dlogits"), _ptr(Wg, f32, self.d * self.E, "Wg"),
+            _ptr(dX, self.elt, self.T * self.d, "dX"), _stream()), "moe_input_grad")
 
 
 class LayerBuffers:

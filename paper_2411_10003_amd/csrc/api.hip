@@ -49,6 +49,7 @@ struct Carve {
     void* act() const { return base + c->off_act; }
     void* dz() const { return base + c->off_dz; }
     void* du() const { return base + c->off_du; }
+    float* gate_part() const { return reinterpret_cast<float*>(base + c->off_gate_part); }
 };
 
 }  // namespace
@@ -73,6 +74,7 @@ int moe_create(moe_handle_t* out, const moe_shape_t* shape)
     c->off_act = off;         off += ah;
     c->off_dz = off;          off += ah;
     c->off_du = off;          off += (shape->act == MOE_ACT_SWIGLU) ? ah : 0;
+    c->off_gate_part = off;   off += align256((size_t)gate_grad_partitions(*shape) * ((size_t)shape->d * shape->E + shape->E) * sizeof(float));
     c->ws_bytes = off;
     *out = c;
     return MOE_OK;
@@ -227,6 +229,25 @@ int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int
 {
     if (!h || !dw || !logits || !idx || !dlogits) return MOE_ERR_NULL;
     return hip_status(launch_gate_bwd(h->s, dw, logits, idx, dlogits, (hipStream_t)stream));
+}
+
+int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, float* dWg, float* dbg, void* ws, void* stream)
+{
+    if (!h || !X || !dlogits || !dWg || !dbg) return MOE_ERR_NULL;
+    if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
+    if (h->s.E > 64) return MOE_ERR_UNIMPLEMENTED;
+    const Carve c{(char*)ws, h};
+    float* part = c.gate_part();
+    float* part_b = part + (size_t)gate_grad_partitions(h->s) * h->s.d * h->s.E;
+    return hip_status(launch_gate_wgrad(h->s, X, dlogits, part, part_b, dWg, dbg, (hipStream_t)stream));
+}
+
+int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const float* dlogits, const float* Wg,
+                   void* dX, void* stream)
+{
+    if (!h || !dXp || !pos || !dlogits || !Wg || !dX) return MOE_ERR_NULL;
+    if (h->s.E > 64) return MOE_ERR_UNIMPLEMENTED;
+    return hip_status(launch_input_grad(h->s, dXp, pos, dlogits, Wg, dX, (hipStream_t)stream));
 }
 
 int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream)

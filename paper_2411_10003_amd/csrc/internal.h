@@ -16,6 +16,7 @@ struct moe_ctx {
     size_t off_act;        // elt [A,h]  activation output A (forward) / recomputed A (backward)
     size_t off_dz;         // elt [A,h]  dZ
     size_t off_du;         // elt [A,h]  dU (SwiGLU)
+    size_t off_gate_part;  // float [partitions][d*E + E] partial sums of the gate parameter gradients
     size_t ws_bytes;
     int n_chunks;          // ceil(A / ROUTE_CHUNK)
     // per-chunk histograms left in a workspace by the last moe_expert_counts: whose they are
@@ -49,6 +50,11 @@ hipError_t launch_combine_bwd(const moe_shape_t& s, const void* dOut, const void
 bool layout_positions_fusable(const moe_shape_t& s, int n_chunks);
 hipError_t launch_layout_positions(const moe_shape_t& s, const int32_t* idx, const int32_t* expert_dest, const int32_t* counts,
                                    const int32_t* chunk_hist, int n_chunks, const moe_layout_t& L, int32_t* status, hipStream_t st);
+int gate_grad_partitions(const moe_shape_t& s);
+hipError_t launch_input_grad(const moe_shape_t& s, const void* dXp, const int32_t* pos, const float* dlogits,
+                             const float* Wg, void* dX, hipStream_t st);
+hipError_t launch_gate_wgrad(const moe_shape_t& s, const void* X, const float* dlogits, float* partial, float* partial_b,
+                             float* dWg, float* dbg, hipStream_t st);
 hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
 hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
 
