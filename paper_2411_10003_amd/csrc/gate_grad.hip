@@ -7,7 +7,11 @@
 // (they stream X or dXp once) with E fp32 FMAs per element beside it; fp32 throughout, E <= 64.
 #include "internal.h"
 
+#include <type_traits>
+
 namespace {
+
+constexpr int MAXK_IG = 8;      // the handle allows k <= 8
 
 __device__ __forceinline__ void unpack_bf16x8(const uint4& v, float* f)
 {
@@ -38,39 +42,59 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
     __syncthreads();
     const int col = c0 + lane * VN;
     const int t_begin = blockIdx.y * tok_per_block, t_end = min(T, t_begin + tok_per_block);
-    for (int t = t_begin + wave; t < t_end; t += n_waves) {
-        float acc[VN];
+    // two tokens per trip, all of their loads issued before the first use
+    constexpr int U = 2;
+    for (int t0 = t_begin + wave; t0 < t_end; t0 += n_waves * U) {
+        float acc[U][VN];
+        uint4 raw[U][MAXK_IG];
 #pragma unroll
-        for (int i = 0; i < VN; ++i) acc[i] = 0.0f;
-        if (col < d) {
-            for (int j = 0; j < k; ++j) {                          // expert path, ascending j
-                const size_t row = (size_t)pos[(size_t)t * k + j];
-                if (VN == 8) {
-                    float f[8];
-                    unpack_bf16x8(*reinterpret_cast<const uint4*>(dXp + row * d + col), f);
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + n_waves * u;
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[i] += f[i];
-                } else {
-                    const float4 f = *reinterpret_cast<const float4*>(dXp + row * d + col);
-                    acc[0] += f.x; acc[1] += f.y; acc[2] += f.z; acc[3] += f.w;
+            for (int j = 0; j < MAXK_IG; ++j)
+                if (j < k && t < t_end && col < d)
+                    raw[u][j] = *reinterpret_cast<const uint4*>(dXp + (size_t)pos[(size_t)t * k + j] * d + col);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + n_waves * u;
+            if (t >= t_end || col >= d) continue;
+#pragma unroll
+            for (int i = 0; i < VN; ++i) acc[u][i] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < MAXK_IG; ++j) {                    // expert path, ascending j
+                if (j < k) {
+                    float f[VN];
+                    if (VN == 8) unpack_bf16x8(raw[u][j], f);
+                    else { f[0] = __uint_as_float(raw[u][j].x); f[1] = __uint_as_float(raw[u][j].y); f[2 % VN] = __uint_as_float(raw[u][j].z); f[3 % VN] = __uint_as_float(raw[u][j].w); }
+#pragma unroll
+                    for (int i = 0; i < VN; ++i) acc[u][i] += f[i];
                 }
             }
             const float* dl = dlogits + (size_t)t * E;             // uniform over the wave
-            for (int e = 0; e < E; ++e) {
-                const float g = dl[e];
-                const float* wrow = wt + e * CW + lane * VN;
+            for (int e0 = 0; e0 < E; e0 += 4) {
+                float gq[4];
+                if (e0 + 4 <= E) { const float4 v = *reinterpret_cast<const float4*>(dl + e0); gq[0] = v.x; gq[1] = v.y; gq[2] = v.z; gq[3] = v.w; }
+                else { for (int q = 0; q < 4; ++q) gq[q] = (e0 + q < E) ? dl[e0 + q] : 0.0f; }
 #pragma unroll
-                for (int i = 0; i < VN; i += 4) {
-                    const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
-                    acc[i + 0] = fmaf(g, wv.x, acc[i + 0]); acc[i + 1] = fmaf(g, wv.y, acc[i + 1]);
-                    acc[i + 2] = fmaf(g, wv.z, acc[i + 2]); acc[i + 3] = fmaf(g, wv.w, acc[i + 3]);
+                for (int q = 0; q < 4; ++q) {
+                    const float g = gq[q];
+                    if (g == 0.0f) continue;                       // renormalised top-k: only k of the E are non-zero
+                    const float* wrow = wt + (e0 + q) * CW + lane * VN;
+#pragma unroll
+                    for (int i = 0; i < VN; i += 4) {
+                        const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
+                        acc[u][i + 0] = fmaf(g, wv.x, acc[u][i + 0]); acc[u][i + 1] = fmaf(g, wv.y, acc[u][i + 1]);
+                        acc[u][i + 2] = fmaf(g, wv.z, acc[u][i + 2]); acc[u][i + 3] = fmaf(g, wv.w, acc[u][i + 3]);
+                    }
                 }
             }
             if (VN == 8) {
                 *reinterpret_cast<uint4*>(dX + (size_t)t * d + col) =
-                    make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]), pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
+                    make_uint4(pack_bf16x2(acc[u][0], acc[u][1]), pack_bf16x2(acc[u][2], acc[u][3]),
+                               pack_bf16x2(acc[u][4 % VN], acc[u][5 % VN]), pack_bf16x2(acc[u][6 % VN], acc[u][7 % VN]));
             } else {
-                *reinterpret_cast<float4*>(dX + (size_t)t * d + col) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                *reinterpret_cast<float4*>(dX + (size_t)t * d + col) = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
             }
         }
     }
@@ -82,7 +106,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
 // writes one partial [strip][E] per token partition.  A second kernel adds the partitions in a fixed
 // order, so the result does not depend on the schedule.
 template <typename ET, int EC, int CPT>
-__global__ __launch_bounds__(256) void gate_wgrad_partial_kernel(
+__global__ __launch_bounds__(256, 2) void gate_wgrad_partial_kernel(
     const ET* __restrict__ X, const float* __restrict__ dlogits, float* __restrict__ partial,
     float* __restrict__ partial_b, int T, int d, int E, int tok_per_part)
 {
@@ -101,33 +125,64 @@ __global__ __launch_bounds__(256) void gate_wgrad_partial_kernel(
 #pragma unroll
         for (int e = 0; e < EC; ++e) acc[i][e] = 0.0f;
     float accb = 0.0f;                                             // lane e: sum of dlogits[:, e]
-    for (int t = t_begin + wave; t < t_end; t += 4) {
-        float x[CPT];
+    // eight tokens per trip: their row pieces are requested before the first use (a wave has little else
+    // in flight: the partial sums take half of its registers).  The E logit gradients of a token are the
+    // same for every lane and come through the scalar cache in 16-byte pieces.
+    constexpr int U = 8;
+    // CPT columns of a row as one load: 16/8/4 bytes of bf16, 16/8 bytes of fp32
+    typedef typename std::conditional<sizeof(ET) * CPT == 16, uint4,
+            typename std::conditional<sizeof(ET) * CPT == 8, uint2, uint32_t>::type>::type raw_t;
+    static_assert(sizeof(ET) * CPT == sizeof(raw_t), "row piece");
+    for (int t0 = t_begin + wave; t0 < t_end; t0 += 4 * U) {
+        raw_t raw[U];
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) x[i] = 0.0f;
-        if (col < d) {
-            if constexpr (sizeof(ET) == 2 && CPT == 8) {
-                unpack_bf16x8(*reinterpret_cast<const uint4*>(X + (size_t)t * d + col), x);
-            } else if constexpr (sizeof(ET) == 2 && CPT == 4) {
-                const uint2 v = *reinterpret_cast<const uint2*>(X + (size_t)t * d + col);
-                x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
-                x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
-            } else if constexpr (sizeof(ET) == 2 && CPT == 2) {
-                const uint32_t v = *reinterpret_cast<const uint32_t*>(X + (size_t)t * d + col);
-                x[0] = __uint_as_float(v << 16); x[1] = __uint_as_float(v & 0xffff0000u);
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + 4 * u;
+            if (t < t_end && col < d) raw[u] = *reinterpret_cast<const raw_t*>(X + (size_t)t * d + col);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + 4 * u;
+            if (t >= t_end) break;
+            float x[CPT];
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) x[i] = 0.0f;
+            if (col < d) {
+                if constexpr (sizeof(ET) == 2 && CPT == 8) {
+                    unpack_bf16x8(raw[u], x);
+                } else if constexpr (sizeof(ET) == 2 && CPT == 4) {
+                    x[0] = __uint_as_float(raw[u].x << 16); x[1] = __uint_as_float(raw[u].x & 0xffff0000u);
+                    x[2] = __uint_as_float(raw[u].y << 16); x[3] = __uint_as_float(raw[u].y & 0xffff0000u);
+                } else if constexpr (sizeof(ET) == 2) {
+                    x[0] = __uint_as_float(raw[u] << 16); x[1] = __uint_as_float(raw[u] & 0xffff0000u);
+                } else if constexpr (CPT == 4) {
+                    x[0] = __uint_as_float(raw[u].x); x[1] = __uint_as_float(raw[u].y);
+                    x[2] = __uint_as_float(raw[u].z); x[3] = __uint_as_float(raw[u].w);
+                } else {
+                    x[0] = __uint_as_float(raw[u].x); x[1] = __uint_as_float(raw[u].y);
+                }
+            }
+            const float* dl = dlogits + (size_t)t * E;             // uniform over the wave
+            float g[EC];
+            if (E == EC) {
+#pragma unroll
+                for (int e = 0; e < EC; e += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(dl + e);
+                    g[e] = v.x; g[e + 1] = v.y; g[e + 2] = v.z; g[e + 3] = v.w;
+                }
             } else {
 #pragma unroll
-                for (int i = 0; i < CPT; ++i) x[i] = reinterpret_cast<const float*>(X)[(size_t)t * d + col + i];
+                for (int e = 0; e < EC; ++e) g[e] = (e < E) ? dl[e] : 0.0f;
+            }
+            if (blockIdx.x == 0 && lane < E) accb += dl[lane];
+#pragma unroll
+            for (int e = 0; e < EC; ++e) {
+                if (g[e] != 0.0f) {                                // uniform; skips the experts a token did not select
+#pragma unroll
+                    for (int i = 0; i < CPT; ++i) acc[i][e] = fmaf(x[i], g[e], acc[i][e]);
+                }
             }
         }
-        const float* dl = dlogits + (size_t)t * E;                 // uniform over the wave
-#pragma unroll
-        for (int e = 0; e < EC; ++e) {
-            const float g = (e < E) ? dl[e] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < CPT; ++i) acc[i][e] = fmaf(x[i], g, acc[i][e]);
-        }
-        if (blockIdx.x == 0 && lane < E) accb += dl[lane];
     }
     // fold the four waves: waves 1, 2, 3 hand their sums to wave 0 one after the other
     for (int w = 1; w < 4; ++w) {
