@@ -159,6 +159,14 @@ int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const vo
                        const moe_layout_t* layout, const void* W1, const void* W2, const void* W3,
                        void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream);
 
+/* As moe_expert_ffn_bwd, but the weight gradients are added to what dW1, dW2, dW3 hold (all G groups;
+ * an empty group adds zero): the form in which a device folds the gradient of a replicated expert into a
+ * buffer that already holds another contribution, as the Agg primitive does across devices (Section 4.1),
+ * and the form gradient accumulation over micro-batches needs.  dXp is overwritten as before. */
+int moe_expert_ffn_bwd_acc(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                           const moe_layout_t* layout, const void* W1, const void* W2, const void* W3,
+                           void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream);
+
 /* Gradient of the send (the backward all-to-all of the dispatch): dX[t,:] = sum_j dXp[pos[t*k+j],:],
  * the expert-path gradient of the layer input.  in: dXp[A,d] elt, pos[A];  out: dX[T,d] elt */
 int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* dX, void* stream);

@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
-    "moe_plan", "moe_gate_bwd_params", "moe_input_grad",
+    "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc",
 ]
 
 
@@ -76,6 +76,7 @@ def load() -> ctypes.CDLL:
         lib.moe_combine.argtypes = [vp] * 6
         lib.moe_combine_bwd.argtypes = [vp] * 8
         lib.moe_expert_ffn_bwd.argtypes = [vp] * 5 + [ctypes.POINTER(_Layout)] + [vp] * 9
+        lib.moe_expert_ffn_bwd_acc.argtypes = [vp] * 5 + [ctypes.POINTER(_Layout)] + [vp] * 9
         lib.moe_dispatch_bwd.argtypes = [vp] * 5
         lib.moe_gate_bwd.argtypes = [vp] * 6
         lib.moe_gate_bwd_params.argtypes = [vp] * 7
@@ -234,14 +235,18 @@ class Handle:
             _ptr(pos, torch.int32, self.A, "pos"), _ptr(w, torch.float32, self.A, "w"),
             _ptr(dYp, e, self.A * self.d, "dYp"), _ptr(dw, torch.float32, self.A, "dw"), _stream()), "moe_combine_bwd")
 
-    def expert_ffn_bwd(self, dYp, Xp, Z, U, layout: Layout, W1, W2, W3, dXp, dW1, dW2, dW3):
+    def expert_ffn_bwd(self, dYp, Xp, Z, U, layout: Layout, W1, W2, W3, dXp, dW1, dW2, dW3, accumulate: bool = False):
         e, f32, dh = self.elt, torch.float32, self.G * self.d * self.h
-        self._check(self.lib.moe_expert_ffn_bwd(
+        fn = self.lib.moe_expert_ffn_bwd_acc if accumulate else self.lib.moe_expert_ffn_bwd
+        self._check(fn(
             self._h, _ptr(dYp, e, self.A * self.d, "dYp"), _ptr(Xp, e, self.A * self.d, "Xp"),
             _ptr(Z, e, self.A * self.h, "Z"), _ptr(U, e, self.A * self.h, "U"), ctypes.byref(layout.c),
             _ptr(W1, e, dh, "W1"), _ptr(W2, e, dh, "W2"), _ptr(W3, e, dh, "W3"),
             _ptr(dXp, e, self.A * self.d, "dXp"), _ptr(dW1, f32, dh, "dW1"), _ptr(dW2, f32, dh, "dW2"),
-            _ptr(dW3, f32, dh, "dW3"), self._ws(), _stream()), "moe_expert_ffn_bwd")
+            _ptr(dW3, f32, dh, "dW3"), self._ws(), _stream()), "moe_expert_ffn_bwd_acc" if accumulate else "moe_expert_ffn_bwd")
+
+    def expert_ffn_bwd_acc(self, *args):
+        self.expert_ffn_bwd(*args, accumulate=True)
 
     def dispatch_bwd(self, dXp, pos, dX):
         self._check(self.lib.moe_dispatch_bwd(

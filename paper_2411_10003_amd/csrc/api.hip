@@ -198,9 +198,9 @@ int moe_combine_bwd(moe_handle_t h, const void* dOut, const void* Yp, const int3
     return hip_status(launch_combine_bwd(h->s, dOut, Yp, pos, w, dYp, dw, (hipStream_t)stream));
 }
 
-int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
-                       const moe_layout_t* L, const void* W1, const void* W2, const void* W3,
-                       void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream)
+static int ffn_bwd_impl(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                        const moe_layout_t* L, const void* W1, const void* W2, const void* W3,
+                        void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream, bool accumulate)
 {
     if (!h || !dYp || !Xp || !Z || !L || !W1 || !W2 || !dXp || !dW1 || !dW2) return MOE_ERR_NULL;
     if (!L->slot_offsets || !L->dest_slots) return MOE_ERR_NULL;
@@ -214,8 +214,23 @@ int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const vo
     a.Z = const_cast<void*>(Z); a.U = const_cast<void*>(U); a.Act = c.act();
     a.dYp = dYp; a.dXp = dXp; a.dZ = c.dz(); a.dU = c.du();
     a.dW1 = dW1; a.dW2 = dW2; a.dW3 = dW3;
+    a.accumulate = accumulate;
     hipStream_t st = (hipStream_t)stream;
     return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_bwd_f32(h->s, a, st) : launch_ffn_bwd_bf16(h->s, a, st));
+}
+
+int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                       const moe_layout_t* L, const void* W1, const void* W2, const void* W3,
+                       void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream)
+{
+    return ffn_bwd_impl(h, dYp, Xp, Z, U, L, W1, W2, W3, dXp, dW1, dW2, dW3, ws, stream, false);
+}
+
+int moe_expert_ffn_bwd_acc(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
+                           const moe_layout_t* L, const void* W1, const void* W2, const void* W3,
+                           void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream)
+{
+    return ffn_bwd_impl(h, dYp, Xp, Z, U, L, W1, W2, W3, dXp, dW1, dW2, dW3, ws, stream, true);
 }
 
 int moe_dispatch_bwd(moe_handle_t h, const void* dXp, const int32_t* pos, void* dX, void* stream)

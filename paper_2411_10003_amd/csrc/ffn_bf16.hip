@@ -51,6 +51,7 @@ struct GemmParams {
     // outputs
     bf16_t *O0, *O1, *O2;        // EPI_BF16: O0.  FWD1: Z, U, Act.  BWD1: dZ, dU, Act
     float* OF;                   // EPI_F32
+    int accumulate;              // EPI_F32: add to the output instead of overwriting it
     long ldo, o_group_stride;
     const bf16_t *Zin, *Uin;     // BWD1: saved pre-activations
 };
@@ -504,6 +505,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
             } else if (EPI == EPI_F32) {
                 float* dst = p.OF + (long)g * p.o_group_stride + o;
+                if (p.accumulate) {
+                    const float4 o0 = *reinterpret_cast<const float4*>(dst), o1 = *reinterpret_cast<const float4*>(dst + 4);
+                    v[0] += o0.x; v[1] += o0.y; v[2] += o0.z; v[3] += o0.w;
+                    v[4] += o1.x; v[5] += o1.y; v[6] += o1.z; v[7] += o1.w;
+                }
                 *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
                 *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
             } else if (EPI == EPI_FWD1_GELU) {
@@ -652,7 +658,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         GemmParams p = base_params(s, a);
         p.A[0] = (const bf16_t*)L; p.B[0] = (const bf16_t*)R;
         p.lda = ldl; p.ldb = ldr; p.b_group_stride = 0; p.Mout = Mout; p.N = N;
-        p.OF = out; p.ldo = N; p.o_group_stride = d * h;
+        p.OF = out; p.ldo = N; p.o_group_stride = d * h; p.accumulate = a.accumulate ? 1 : 0;
         return launch<KIND_TN, EPI_F32>(p, A, s.G, st);
     };
     e = wgrad(a.Xp, d, s.d, a.dZ, h, s.h, a.dW1);

@@ -24,6 +24,7 @@ struct F32Args {
     int self, Gcap, act, d, h;
     const float *Xp, *W1, *W2, *W3, *dYp, *Zc, *Uc, *Actc, *dZc, *dUc;
     float *Yp, *Z, *U, *Act, *dZ, *dU, *dXp, *dW1, *dW2, *dW3;
+    int accumulate;
 };
 
 // acc (+acc2) = sum_k A(m,k) B(k,n) (+ A2(m,k) B2(k,n)) over a TS x TS output tile
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(TS * TS) void ffn_f32_kernel(F32Args a)
         View B{Rp + (long)row0 * No, No, 1};            // B(r, n) = R[row0 + r, n]
         tile_gemm(A, B, A, B, false, m, n, Mo, No, rows, acc, acc2);
         float* out = (which == 1) ? a.dW1 : (which == 3 ? a.dW3 : a.dW2);
-        if (m < Mo && n < No) out[wdh + (long)m * No + n] = acc;
+        if (m < Mo && n < No) out[wdh + (long)m * No + n] = a.accumulate ? out[wdh + (long)m * No + n] + acc : acc;
         return;
     }
 
@@ -146,6 +147,7 @@ F32Args make_args(const moe_shape_t& s, const ffn_args& a)
     f.Yp = (float*)a.Yp; f.Z = (float*)a.Z; f.U = (float*)a.U; f.Act = (float*)a.Act;
     f.dZ = (float*)a.dZ; f.dU = (float*)a.dU; f.dXp = (float*)a.dXp;
     f.dW1 = a.dW1; f.dW2 = a.dW2; f.dW3 = a.dW3;
+    f.accumulate = a.accumulate ? 1 : 0;
     return f;
 }
 

@@ -65,6 +65,7 @@ struct ffn_args {
     const void* dYp;                   // backward
     void *dXp, *dZ, *dU;               // dZ, dU in workspace
     float *dW1, *dW2, *dW3;
+    bool accumulate = false;           // weight gradients are added to what dW holds instead of overwriting it
 };
 hipError_t launch_ffn_fwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
 hipError_t launch_ffn_bwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);

@@ -257,6 +257,31 @@ def test_backward_calls(G, orc, cfg):
         if e == o:
             assert not G.host(b.dW1)[g].any() and not G.host(b.dW2)[g].any()
 
+    # --- accumulate form: a second contribution is added to what the buffers hold.  Doubling is exact in
+    # fp32, so running the same backward again on top must give exactly twice the first result; seeding the
+    # buffers with another value checks against the oracle's sum.
+    first = [t.clone() if t is not None else None for t in (b.dW1, b.dW2, b.dW3)]
+    dXp_first = b.dXp.clone()
+    hd.expert_ffn_bwd_acc(G.dev(dYp_in, dt), b.Xp, b.Z, b.U, b.layout, case.dW1, case.dW2, case.dW3,
+                          b.dXp, b.dW1, b.dW2, b.dW3)
+    torch.cuda.synchronize()
+    assert torch.equal(b.dW1, first[0] * 2) and torch.equal(b.dW2, first[1] * 2)
+    if cfg.act == "swiglu":
+        assert torch.equal(b.dW3, first[2] * 2)
+    assert torch.equal(b.dXp, dXp_first)                          # the row gradient is overwritten as before
+    b.dW1.fill_(0.5); b.dW2.fill_(-0.25)
+    if b.dW3 is not None:
+        b.dW3.fill_(2.0)
+    hd.expert_ffn_bwd_acc(G.dev(dYp_in, dt), b.Xp, b.Z, b.U, b.layout, case.dW1, case.dW2, case.dW3,
+                          b.dXp, b.dW1, b.dW2, b.dW3)
+    torch.cuda.synchronize()
+    assert G.rel_l2(G.host(b.dW1)[:Gn] - 0.5, dW1o[:Gn]) <= tol
+    assert G.rel_l2(G.host(b.dW2)[:Gn] + 0.25, dW2o[:Gn]) <= tol
+    for g in range(cfg.G_max):                                   # an empty or unused group adds zero
+        o, e = case.group_rows(g) if g < Gn else (0, 0)
+        if e == o:
+            assert (G.host(b.dW1)[g] == 0.5).all() and (G.host(b.dW2)[g] == -0.25).all()
+
     # --- dispatch_bwd and gate_bwd on shared inputs
     dXp_in = inp["dXp_fill"].copy()
     hd.dispatch_bwd(G.dev(dXp_in, dt), G.dev(pos), b.dX)
