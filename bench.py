@@ -264,6 +264,27 @@ def main():
             per_call[name] = {"ms": round(ms, 4), "in_step": False, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                               "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
+    # Trans on one GPU: gather the hosted experts' parameters from a pool of all experts into the group slots
+    # (worst case: every slot changes; a slot that already holds its expert is skipped)
+    if dt == "bf16":
+        n_t = cfg.n_mats
+        pools = [torch.empty(E, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
+        slots = [torch.empty(cfg.G_max, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
+        slot_expert = torch.full((cfg.G_max,), -1, dtype=torch.int32, device=dev)
+        hd.trans(expert_dest, slot_expert, pools, slots)
+        torch.cuda.synchronize()
+        te = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        slot_expert.fill_(-1)
+        te[0].record(); hd.trans(expert_dest, slot_expert, pools, slots); te[1].record()
+        hd.trans(expert_dest, slot_expert, pools, slots); te[2].record()          # nothing to move the second time
+        torch.cuda.synchronize()
+        moved = 2.0 * len(group_rows) * n_t * d * h * es
+        ms_all, ms_none = te[0].elapsed_time(te[1]), te[1].elapsed_time(te[2])
+        per_call["trans"] = {"ms": round(ms_all, 4), "in_step": False, "GB/s": round(moved / (ms_all * 1e-3) / 1e9, 1),
+                             "hbm_frac": round(moved / (ms_all * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                             "ms_when_nothing_moves": round(ms_none, 4)}
+        del pools, slots
+
     result = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,

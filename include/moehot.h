@@ -191,6 +191,19 @@ int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, flo
 int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const float* dlogits, const float* Wg,
                    void* dX, void* stream);
 
+/* Trans on one GPU (Section 4.1: the parameters of a selected expert are transferred to the devices that
+ * compute its inputs).  With the parameters of all E experts in pools in this GPU's memory, the transfer is
+ * a gather of the hosted experts into the G group slots that moe_expert_ffn_fwd/bwd read, driven by the
+ * plan as it lies in device memory: group g receives the g-th expert e (ascending) with
+ * expert_dest[e] == self.  A slot that already holds that expert is not copied again.
+ *   in    : expert_dest[E] int32 (device); n_tensors (1..8) and, on the HOST, arrays of n_tensors device
+ *           pointers pools[i] ([E] experts of bytes_per_expert[i] bytes each, a multiple of 16, 16-byte aligned)
+ *   in/out: slot_expert[G] int32 (device): the expert each slot holds, -1 for none; updated after the copies
+ *   out   : groups[i] ([G] slots of bytes_per_expert[i] bytes); slots beyond the hosted experts keep their contents
+ * More hosted experts than G is the caller's error (moe_dispatch reports it through moe_read_status). */
+int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, int n_tensors,
+              const void* const* pools, void* const* groups, const size_t* bytes_per_expert, void* stream);
+
 /* ---- planner (Sections 4.2-4.3 and 5.3 of the paper) ------------------------------------------
  *
  * moe_plan runs the paper's greedy search for a lightweight expert placement (Algorithm 1) on the

@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
-    "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc",
+    "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans",
 ]
 
 
@@ -81,6 +81,7 @@ def load() -> ctypes.CDLL:
         lib.moe_gate_bwd.argtypes = [vp] * 6
         lib.moe_gate_bwd_params.argtypes = [vp] * 7
         lib.moe_input_grad.argtypes = [vp] * 7
+        lib.moe_trans.argtypes = [vp, vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
         lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
     return _lib
@@ -258,6 +259,22 @@ class Handle:
         self._check(self.lib.moe_gate_bwd(
             self._h, _ptr(dw, f32, self.A, "dw"), _ptr(logits, f32, self.T * self.E, "logits"),
             _ptr(idx, torch.int32, self.A, "idx"), _ptr(dlogits, f32, self.T * self.E, "dlogits"), _stream()), "moe_gate_bwd")
+
+    def trans(self, expert_dest, slot_expert, pools, groups):
+        """moe_trans: gather the hosted experts' tensors from the pools into the group slots."""
+        n = len(pools)
+        per = [p.numel() // self.E * p.element_size() for p in pools]
+        for p, g, b in zip(pools, groups, per):
+            if not (p.is_cuda and g.is_cuda and p.is_contiguous() and g.is_contiguous()):
+                raise ValueError("trans: need contiguous device tensors")
+            if p.numel() % self.E or g.numel() * g.element_size() < self.G * b or p.dtype != g.dtype:
+                raise ValueError("trans: pool / group sizes do not match")
+        pa = (ctypes.c_void_p * n)(*(p.data_ptr() for p in pools))
+        ga = (ctypes.c_void_p * n)(*(g.data_ptr() for g in groups))
+        ba = (ctypes.c_size_t * n)(*per)
+        self._check(self.lib.moe_trans(
+            self._h, _ptr(expert_dest, torch.int32, self.E, "expert_dest"), _ptr(slot_expert, torch.int32, self.G, "slot_expert"),
+            n, pa, ga, ba, _stream()), "moe_trans")
 
     def gate_bwd_params(self, X, dlogits, dWg, dbg):
         f32 = torch.float32

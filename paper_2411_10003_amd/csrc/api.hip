@@ -265,6 +265,24 @@ int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const fl
     return hip_status(launch_input_grad(h->s, dXp, pos, dlogits, Wg, dX, (hipStream_t)stream));
 }
 
+int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, int n_tensors,
+              const void* const* pools, void* const* groups, const size_t* bytes_per_expert, void* stream)
+{
+    if (!h || !expert_dest || !slot_expert || !pools || !groups || !bytes_per_expert) return MOE_ERR_NULL;
+    if (n_tensors < 1 || n_tensors > 8) return MOE_ERR_SHAPE;
+    for (int i = 0; i < n_tensors; ++i) {
+        if (!pools[i] || !groups[i]) return MOE_ERR_NULL;
+        if (bytes_per_expert[i] == 0 || bytes_per_expert[i] % 16 != 0) return MOE_ERR_SHAPE;
+        if ((reinterpret_cast<uintptr_t>(pools[i]) | reinterpret_cast<uintptr_t>(groups[i])) & 15) return MOE_ERR_SHAPE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < n_tensors && e == hipSuccess; ++i)
+        e = launch_trans_gather(h->s, expert_dest, slot_expert, pools[i], groups[i], (long)bytes_per_expert[i], st);
+    if (e == hipSuccess) e = launch_trans_commit(h->s, expert_dest, slot_expert, st);
+    return hip_status(e);
+}
+
 int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream)
 {
     if (!cfg || !gating || !out) return MOE_ERR_NULL;

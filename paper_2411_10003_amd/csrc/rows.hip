@@ -311,3 +311,75 @@ hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int3
         hipLaunchKernelGGL((dispatch_bwd_kernel<bf16_t, 0>), g, b, 0, st, (const bf16_t*)dXp, pos, (bf16_t*)dX, s.T, s.d, s.k);
     return hipGetLastError();
 }
+
+// ---- Trans on one GPU (Section 4.1: the parameters of a selected expert are transferred to the devices
+// that will compute its inputs).  With every expert's parameters in one pool in this GPU's memory, the
+// transfer is a gather of the hosted experts into the group slots the grouped FFN reads, driven by the
+// plan as it lies in device memory: group g is the g-th expert e (ascending) with expert_dest[e] == self.
+// A slot that already holds the right expert is left alone (placements change little from one iteration to
+// the next, Section 3), which slot_expert[G] keeps track of.
+namespace {
+
+__device__ __forceinline__ int hosted_expert_of_group(const int32_t* __restrict__ expert_dest, int E, int self, int g)
+{
+    // wave-uniform scan; E <= 1024
+    int seen = 0;
+    for (int e = 0; e < E; ++e) {
+        if (expert_dest[e] == self) {
+            if (seen == g) return e;
+            ++seen;
+        }
+    }
+    return -1;
+}
+
+__global__ __launch_bounds__(256) void trans_gather_kernel(
+    const int32_t* __restrict__ expert_dest, const int32_t* __restrict__ slot_expert,
+    const uint4* __restrict__ pool, uint4* __restrict__ groups, long vec_per_expert, int E, int self)
+{
+    const int g = blockIdx.y;
+    const int e = hosted_expert_of_group(expert_dest, E, self, g);
+    if (e < 0 || e == slot_expert[g]) return;              // unused slot, or the expert is already there
+    const uint4* src = pool + (long)e * vec_per_expert;
+    uint4* dst = groups + (long)g * vec_per_expert;
+    const long stride = (long)gridDim.x * blockDim.x * 4;
+    for (long v = ((long)blockIdx.x * blockDim.x + threadIdx.x); v < vec_per_expert; v += stride) {
+        uint4 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long i = v + (long)u * gridDim.x * blockDim.x;
+            if (i < vec_per_expert) r[u] = src[i];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const long i = v + (long)u * gridDim.x * blockDim.x;
+            if (i < vec_per_expert) dst[i] = r[u];
+        }
+    }
+}
+
+__global__ void trans_commit_kernel(const int32_t* __restrict__ expert_dest, int32_t* __restrict__ slot_expert, int E, int self, int G)
+{
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= G) return;
+    const int e = hosted_expert_of_group(expert_dest, E, self, g);
+    if (e >= 0) slot_expert[g] = e;                        // an unused slot keeps what it holds
+}
+
+}  // namespace
+
+hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* slot_expert,
+                               const void* pool, void* groups, long bytes_per_expert, hipStream_t st)
+{
+    const long vec = bytes_per_expert / 16;
+    const int bx = (int)((vec + 256 * 4 - 1) / (256 * 4) < 512 ? (vec + 256 * 4 - 1) / (256 * 4) : 512);
+    hipLaunchKernelGGL(trans_gather_kernel, dim3(bx > 0 ? bx : 1, s.G), dim3(256), 0, st, expert_dest, slot_expert,
+                       (const uint4*)pool, (uint4*)groups, vec, s.E, s.self);
+    return hipGetLastError();
+}
+
+hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, int32_t* slot_expert, hipStream_t st)
+{
+    hipLaunchKernelGGL(trans_commit_kernel, dim3((s.G + 63) / 64), dim3(64), 0, st, expert_dest, slot_expert, s.E, s.self, s.G);
+    return hipGetLastError();
+}
