@@ -25,7 +25,7 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4& v, float* f)
 // A block owns a strip of 64*VN columns and TOK_PER_BLOCK tokens.  The strip of Wg is staged once per
 // block in LDS, transposed to [e][column] so that a lane reads the VN weights of its columns with
 // 16-byte LDS loads; the E logit gradients of a token are the same for every lane (scalar loads).
-template <typename ET, int VN>
+template <typename ET, int VN, int EC>
 __global__ __launch_bounds__(256) void input_grad_kernel(
     const ET* __restrict__ dXp, const int32_t* __restrict__ pos, const float* __restrict__ dlogits,
     const float* __restrict__ Wg, ET* __restrict__ dX, int T, int d, int E, int k, int tok_per_block)
@@ -42,11 +42,21 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
     __syncthreads();
     const int col = c0 + lane * VN;
     const int t_begin = blockIdx.y * tok_per_block, t_end = min(T, t_begin + tok_per_block);
-    // two tokens per trip, all of their loads issued before the first use
-    constexpr int U = 2;
+    // several tokens per trip, all of their loads issued before the first use.  The U x E logit gradients
+    // of a trip are fetched by the lanes as one flat array and handed out with readlane, so a token costs
+    // no dependent memory round trip of its own.
+    constexpr int U = EC <= 16 ? 4 : 2;
+    constexpr int NDL = (U * EC + 63) / 64;
     for (int t0 = t_begin + wave; t0 < t_end; t0 += n_waves * U) {
         float acc[U][VN];
         uint4 raw[U][MAXK_IG];
+        float dlv[NDL];
+#pragma unroll
+        for (int q = 0; q < NDL; ++q) {
+            const int f = q * 64 + lane, u = f / EC, e = f % EC;
+            const int t = t0 + n_waves * u;
+            dlv[q] = (u < U && t < t_end && e < E) ? dlogits[(size_t)t * E + e] : 0.0f;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + n_waves * u;
@@ -71,22 +81,17 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
                     for (int i = 0; i < VN; ++i) acc[u][i] += f[i];
                 }
             }
-            const float* dl = dlogits + (size_t)t * E;             // uniform over the wave
-            for (int e0 = 0; e0 < E; e0 += 4) {
-                float gq[4];
-                if (e0 + 4 <= E) { const float4 v = *reinterpret_cast<const float4*>(dl + e0); gq[0] = v.x; gq[1] = v.y; gq[2] = v.z; gq[3] = v.w; }
-                else { for (int q = 0; q < 4; ++q) gq[q] = (e0 + q < E) ? dl[e0 + q] : 0.0f; }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float g = gq[q];
-                    if (g == 0.0f) continue;                       // renormalised top-k: only k of the E are non-zero
-                    const float* wrow = wt + (e0 + q) * CW + lane * VN;
+            for (int e = 0; e < EC; ++e) {
+                const int f = u * EC + e;                          // position in the flat [U][EC] array
+                const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dlv[f / 64]), f % 64));
+                if (g == 0.0f) continue;                           // renormalised top-k: only k of the E are non-zero
+                const float* wrow = wt + e * CW + lane * VN;
 #pragma unroll
-                    for (int i = 0; i < VN; i += 4) {
-                        const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
-                        acc[u][i + 0] = fmaf(g, wv.x, acc[u][i + 0]); acc[u][i + 1] = fmaf(g, wv.y, acc[u][i + 1]);
-                        acc[u][i + 2] = fmaf(g, wv.z, acc[u][i + 2]); acc[u][i + 3] = fmaf(g, wv.w, acc[u][i + 3]);
-                    }
+                for (int i = 0; i < VN; i += 4) {
+                    const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
+                    acc[u][i + 0] = fmaf(g, wv.x, acc[u][i + 0]); acc[u][i + 1] = fmaf(g, wv.y, acc[u][i + 1]);
+                    acc[u][i + 2] = fmaf(g, wv.z, acc[u][i + 2]); acc[u][i + 3] = fmaf(g, wv.w, acc[u][i + 3]);
                 }
             }
             if (VN == 8) {
@@ -125,16 +130,26 @@ __global__ __launch_bounds__(256, 2) void gate_wgrad_partial_kernel(
 #pragma unroll
         for (int e = 0; e < EC; ++e) acc[i][e] = 0.0f;
     float accb = 0.0f;                                             // lane e: sum of dlogits[:, e]
-    // eight tokens per trip: their row pieces are requested before the first use (a wave has little else
-    // in flight: the partial sums take half of its registers).  The E logit gradients of a token are the
-    // same for every lane and come through the scalar cache in 16-byte pieces.
+    // eight tokens per trip: their row pieces and their logit gradients are requested before the first use
+    // (a wave has little else in flight: the partial sums take half of its registers).  The U x E logit
+    // gradients of a trip are fetched by the lanes as one flat array (a token's row is one 32..256-byte
+    // piece of dlogits) and handed out with readlane, so a token costs no dependent memory round trip.
     constexpr int U = 8;
+    constexpr int NDL = U * EC / 64;                               // flat loads of logit gradients per trip
+    static_assert(U * EC % 64 == 0 && 64 % EC == 0, "flat layout of the logit gradients");
     // CPT columns of a row as one load: 16/8/4 bytes of bf16, 16/8 bytes of fp32
     typedef typename std::conditional<sizeof(ET) * CPT == 16, uint4,
             typename std::conditional<sizeof(ET) * CPT == 8, uint2, uint32_t>::type>::type raw_t;
     static_assert(sizeof(ET) * CPT == sizeof(raw_t), "row piece");
     for (int t0 = t_begin + wave; t0 < t_end; t0 += 4 * U) {
         raw_t raw[U];
+        float dlv[NDL];
+#pragma unroll
+        for (int q = 0; q < NDL; ++q) {
+            const int f = q * 64 + lane, u = f / EC, e = f % EC;
+            const int t = t0 + 4 * u;
+            dlv[q] = (t < t_end && e < E) ? dlogits[(size_t)t * E + e] : 0.0f;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int t = t0 + 4 * u;
@@ -162,28 +177,23 @@ __global__ __launch_bounds__(256, 2) void gate_wgrad_partial_kernel(
                     x[0] = __uint_as_float(raw[u].x); x[1] = __uint_as_float(raw[u].y);
                 }
             }
-            const float* dl = dlogits + (size_t)t * E;             // uniform over the wave
-            float g[EC];
-            if (E == EC) {
-#pragma unroll
-                for (int e = 0; e < EC; e += 4) {
-                    const float4 v = *reinterpret_cast<const float4*>(dl + e);
-                    g[e] = v.x; g[e + 1] = v.y; g[e + 2] = v.z; g[e + 3] = v.w;
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < EC; ++e) g[e] = (e < E) ? dl[e] : 0.0f;
-            }
-            if (blockIdx.x == 0 && lane < E) accb += dl[lane];
 #pragma unroll
             for (int e = 0; e < EC; ++e) {
-                if (g[e] != 0.0f) {                                // uniform; skips the experts a token did not select
+                const int f = u * EC + e;                          // position in the flat [U][EC] array
+                const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dlv[f / 64]), f % 64));
+                if (g != 0.0f) {                                   // uniform; skips the experts a token did not select
 #pragma unroll
-                    for (int i = 0; i < CPT; ++i) acc[i][e] = fmaf(x[i], g[e], acc[i][e]);
+                    for (int i = 0; i < CPT; ++i) acc[i][e] = fmaf(x[i], g, acc[i][e]);
                 }
             }
         }
+        if (blockIdx.x == 0) {
+#pragma unroll
+            for (int q = 0; q < NDL; ++q) accb += dlv[q];          // lane l always meets expert l % EC
+        }
     }
+    // lanes with the same l % EC hold pieces of the same bias gradient
+    for (int off = EC; off < 64; off <<= 1) accb += __shfl_xor(accb, off, 64);
     // fold the four waves: waves 1, 2, 3 hand their sums to wave 0 one after the other
     for (int w = 1; w < 4; ++w) {
         if (wave == w) {
@@ -243,34 +253,32 @@ hipError_t launch_wgrad_t(const moe_shape_t& s, const void* X, const float* dlog
 
 int gate_grad_partitions(const moe_shape_t& s) { return s.T < 64 * 256 ? (s.T + 255) / 256 : 64; }
 
+template <typename ET, int VN, int EC>
+hipError_t launch_input_grad_t(const moe_shape_t& s, const void* dXp, const int32_t* pos, const float* dlogits,
+                               const float* Wg, void* dX, hipStream_t st)
+{
+    constexpr int CW = 64 * VN, TOK = 128;
+    const dim3 grid((s.d + CW - 1) / CW, (s.T + TOK - 1) / TOK);
+    const size_t lds = (size_t)s.E * CW * sizeof(float);
+    auto kern = input_grad_kernel<ET, VN, EC>;
+    static bool configured = false;      // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * CW * 4);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const ET*)dXp, pos, dlogits, Wg, (ET*)dX, s.T, s.d, s.E, s.k, TOK);
+    return hipGetLastError();
+}
+
 hipError_t launch_input_grad(const moe_shape_t& s, const void* dXp, const int32_t* pos, const float* dlogits,
                              const float* Wg, void* dX, hipStream_t st)
 {
-    const int vn = s.dtype == MOE_BF16 ? 8 : 4;
-    const int cw = 64 * vn;
-    const int tok = 128;
-    const dim3 grid((s.d + cw - 1) / cw, (s.T + tok - 1) / tok);
-    const size_t lds = (size_t)s.E * cw * sizeof(float);
-    if (s.dtype == MOE_BF16) {
-        auto kern = input_grad_kernel<bf16_t, 8>;
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 512 * 4);
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const bf16_t*)dXp, pos, dlogits, Wg, (bf16_t*)dX, s.T, s.d, s.E, s.k, tok);
-    } else {
-        auto kern = input_grad_kernel<float, 4>;
-        static bool configured = false;
-        if (!configured) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 256 * 4);
-            if (e != hipSuccess) return e;
-            configured = true;
-        }
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const float*)dXp, pos, dlogits, Wg, (float*)dX, s.T, s.d, s.E, s.k, tok);
-    }
-    return hipGetLastError();
+    const bool bf = s.dtype == MOE_BF16;
+    if (s.E <= 8)  return bf ? launch_input_grad_t<bf16_t, 8, 8>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_t<float, 4, 8>(s, dXp, pos, dlogits, Wg, dX, st);
+    if (s.E <= 16) return bf ? launch_input_grad_t<bf16_t, 8, 16>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_t<float, 4, 16>(s, dXp, pos, dlogits, Wg, dX, st);
+    if (s.E <= 32) return bf ? launch_input_grad_t<bf16_t, 8, 32>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_t<float, 4, 32>(s, dXp, pos, dlogits, Wg, dX, st);
+    return bf ? launch_input_grad_t<bf16_t, 8, 64>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_t<float, 4, 64>(s, dXp, pos, dlogits, Wg, dX, st);
 }
 
 hipError_t launch_gate_wgrad(const moe_shape_t& s, const void* X, const float* dlogits, float* partial, float* partial_b,
