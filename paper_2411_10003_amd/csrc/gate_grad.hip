@@ -30,14 +30,17 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
     const ET* __restrict__ dXp, const int32_t* __restrict__ pos, const float* __restrict__ dlogits,
     const float* __restrict__ Wg, ET* __restrict__ dX, int T, int d, int E, int k, int tok_per_block)
 {
-    extern __shared__ __attribute__((aligned(16))) float wt[];      // [E][64*VN]
-    constexpr int CW = 64 * VN;
+    extern __shared__ __attribute__((aligned(16))) float wt[];      // [E][64*VN + 4]
+    constexpr int CW = 64 * VN, WP = CW + 4;                       // strip width, padded row of wt
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = blockDim.x >> 6;
     const int c0 = blockIdx.x * CW;                                // first column of the strip
-    for (int i = tid; i < CW * E; i += blockDim.x) {               // Wg[c0 + c][e], read in memory order
+    // Wg[c0 + c][e] -> wt[e][c], read in memory order; the rows of wt are 4 floats longer than the strip so
+    // that the 16..64 experts of a column and the columns next to it fall into different banks
+#pragma unroll 4
+    for (int i = tid; i < CW * E; i += blockDim.x) {
         const int c = i / E, e = i - c * E;
-        wt[e * CW + c] = (c0 + c < d) ? Wg[(size_t)(c0 + c) * E + e] : 0.0f;
+        wt[e * WP + c] = (c0 + c < d) ? Wg[(size_t)(c0 + c) * E + e] : 0.0f;
     }
     __syncthreads();
     const int col = c0 + lane * VN;
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
             const int t = t0 + n_waves * u;
 #pragma unroll
             for (int j = 0; j < MAXK_IG; ++j)
-                if (j < k && t < t_end && col < d)
+                if (j < k && t < t_end && col < d)       // pos comes through the scalar cache (16 tokens per line)
                     raw[u][j] = *reinterpret_cast<const uint4*>(dXp + (size_t)pos[(size_t)t * k + j] * d + col);
         }
 #pragma unroll
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(256) void input_grad_kernel(
                 const int f = u * EC + e;                          // position in the flat [U][EC] array
                 const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dlv[f / 64]), f % 64));
                 if (g == 0.0f) continue;                           // renormalised top-k: only k of the E are non-zero
-                const float* wrow = wt + e * CW + lane * VN;
+                const float* wrow = wt + e * WP + lane * VN;
 #pragma unroll
                 for (int i = 0; i < VN; i += 4) {
                     const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
@@ -259,11 +262,11 @@ hipError_t launch_input_grad_t(const moe_shape_t& s, const void* dXp, const int3
 {
     constexpr int CW = 64 * VN, TOK = 128;
     const dim3 grid((s.d + CW - 1) / CW, (s.T + TOK - 1) / TOK);
-    const size_t lds = (size_t)s.E * CW * sizeof(float);
+    const size_t lds = (size_t)s.E * (CW + 4) * sizeof(float);
     auto kern = input_grad_kernel<ET, VN, EC>;
     static bool configured = false;      // per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * CW * 4);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * (CW + 4) * 4);
         if (e != hipSuccess) return e;
         configured = true;
     }
