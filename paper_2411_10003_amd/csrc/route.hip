@@ -177,10 +177,42 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void layout_positions_kernel(
     __shared__ int32_t next_all[ROUTE_WAVES][FUSED_MAX_E];
     __shared__ int32_t flag;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.x * ROUTE_WAVES + wave;
+    // every load that does not depend on the layout is issued first, so that the kernel pays one memory
+    // round trip and not one per stage: placement and counts, this wave's assignments, and the histograms of
+    // the chunks before it
+    int my_dest = 0, my_count = 0;
+    if (tid < E) { my_dest = expert_dest[tid]; my_count = counts[tid]; }
+    int e_of[ROUTE_CHUNK / 64];
+#pragma unroll
+    for (int r = 0; r < ROUTE_CHUNK / 64; ++r) {
+        const int a = chunk * ROUTE_CHUNK + r * 64 + lane;
+        int e = -1;
+        if (chunk < n_chunks && a < A) {
+            e = idx[a];
+            if (e < 0 || e >= E) e = -1;
+        }
+        e_of[r] = e;
+    }
+    // rows of every expert in the chunks before this one.  The histograms of those chunks are one flat array
+    // of 16-byte pieces, q = E/4 per chunk; q divides 64, so a lane striding by 64 always meets the same four
+    // experts and all of its loads are independent.
+    const int q = E >> 2;
+    int4 acc = make_int4(0, 0, 0, 0);
+    if (chunk < n_chunks) {
+        const int4* hp = reinterpret_cast<const int4*>(chunk_hist);
+        const int n4 = chunk * q;
+#pragma unroll 4
+        for (int i = lane; i < n4; i += 64) {
+            const int4 v = hp[i];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+
     if (tid == 0) flag = 0;
     __syncthreads();
     if (tid < E) {
-        int p = expert_dest[tid];
+        int p = my_dest;
         if (p < 0 || p >= P) { atomicOr(&flag, 1); p = p < 0 ? 0 : P - 1; }
         dest[tid] = p;
     }
@@ -190,7 +222,7 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void layout_positions_kernel(
         int sl = 0;
         for (int f = 0; f < E; ++f) sl += (dest[f] < p) || (dest[f] == p && f < tid);
         slot_of[tid] = sl;
-        slot_cnt[sl] = counts[tid];
+        slot_cnt[sl] = my_count;
     }
     __syncthreads();
     if (wave == 0) {                                        // exclusive scan of the slot counts (E <= 64: one wave)
@@ -219,54 +251,37 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void layout_positions_kernel(
             *status = (flag || hosted > Gcap) ? (int32_t)MOE_ERR_PLAN : (int32_t)MOE_OK;
         }
     }
-    const int chunk = blockIdx.x * ROUTE_WAVES + wave;
     if (chunk >= n_chunks) return;
-    volatile int32_t* next = next_all[wave];
-    {   // rows of every expert in the chunks before this one.  The histograms of those chunks are one
-        // flat array of 16-byte pieces, q = E/4 per chunk; q divides 64, so a lane striding by 64 always
-        // meets the same four experts and all of its loads are independent.
-        const int q = E >> 2;
-        const int4* hp = reinterpret_cast<const int4*>(chunk_hist);
-        const int n4 = chunk * q;
-        int4 acc = make_int4(0, 0, 0, 0);
-#pragma unroll 4
-        for (int i = lane; i < n4; i += 64) {
-            const int4 v = hp[i];
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-        }
-        for (int off = q; off < 64; off <<= 1) {
-            acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
-            acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
-        }
-        if (lane < q) {
-            const int e = 4 * lane;
-            next[e + 0] = slot_off[slot_of[e + 0]] + acc.x;
-            next[e + 1] = slot_off[slot_of[e + 1]] + acc.y;
-            next[e + 2] = slot_off[slot_of[e + 2]] + acc.z;
-            next[e + 3] = slot_off[slot_of[e + 3]] + acc.w;
-        }
+    for (int off = q; off < 64; off <<= 1) {
+        acc.x += __shfl_xor(acc.x, off, 64); acc.y += __shfl_xor(acc.y, off, 64);
+        acc.z += __shfl_xor(acc.z, off, 64); acc.w += __shfl_xor(acc.w, off, 64);
     }
+    // lane e keeps the next free row of expert e (E <= 64); lanes 0..q-1 hold the sums of experts 4l..4l+3
+    int32_t* nx = next_all[wave];
+    if (lane < q) { nx[4 * lane + 0] = acc.x; nx[4 * lane + 1] = acc.y; nx[4 * lane + 2] = acc.z; nx[4 * lane + 3] = acc.w; }
+    __builtin_amdgcn_wave_barrier();
+    int next_row = 0;
+    if (lane < E) next_row = slot_off[slot_of[lane]] + reinterpret_cast<volatile int32_t*>(nx)[lane];
+    // One ballot per expert instead of one per distinct expert met: no data-dependent loop and nothing that
+    // waits on LDS inside it.
+#pragma unroll
     for (int r = 0; r < ROUTE_CHUNK / 64; ++r) {
         const int a = chunk * ROUTE_CHUNK + r * 64 + lane;
-        int e = -1;
-        if (a < A) {
-            e = idx[a];
-            if (e < 0 || e >= E) e = -1;
-        }
-        unsigned long long active = __ballot(e >= 0);
-        while (active) {
-            const int leader = __ffsll((long long)active) - 1;
-            const int e0 = __shfl(e, leader, 64);
+        const int e = e_of[r];
+        unsigned long long mine = 0ull;
+        int add = 0;
+        for (int e0 = 0; e0 < E; ++e0) {
             const unsigned long long m = __ballot(e == e0);
-            const int base = next[e0];
-            if (e == e0) {
-                const int row = base + __popcll(m & lanemask_lt(lane));
-                pos[a] = row;
-                perm[row] = a;
-            }
-            if (lane == leader) next[e0] = base + __popcll(m);
-            active &= ~m;
+            if (e == e0) mine = m;
+            if (lane == e0) add = __popcll(m);
         }
+        const int base = __shfl(next_row, e < 0 ? 0 : e, 64);
+        if (e >= 0) {
+            const int row = base + __popcll(mine & lanemask_lt(lane));
+            pos[a] = row;
+            perm[row] = a;
+        }
+        next_row += add;
     }
 }
 

@@ -84,3 +84,26 @@ def test_plan_validates_arguments(lib):
     c = _Planner(*(good[n] for n, _ in _Planner._fields_))
     assert lib.moe_plan(ctypes.byref(c), ctypes.c_void_p(0x1000), ctypes.byref(missing), None) == -1
 
+
+def test_trans_validates_arguments(lib):
+    """moe_trans checks tensor counts, sizes and alignment on the host (no GPU needed: every call fails early)."""
+    from paper_2411_10003_amd.binding import _Shape
+    shp = _Shape(64, 64, 128, 8, 2, 4, 0, 2, 1, 0, 1)
+    h = ctypes.c_void_p()
+    assert lib.moe_create(ctypes.byref(h), ctypes.byref(shp)) == 0
+    vp = ctypes.c_void_p
+    pools = (vp * 2)(0x1000, 0x2000)
+    groups = (vp * 2)(0x3000, 0x4000)
+    sizes = (ctypes.c_size_t * 2)(4096, 4096)
+    dest, slots = vp(0x5000), vp(0x6000)
+    assert lib.moe_trans(h, None, slots, 2, pools, groups, sizes, None) == -1
+    assert lib.moe_trans(h, dest, slots, 0, pools, groups, sizes, None) == -2
+    assert lib.moe_trans(h, dest, slots, 9, pools, groups, sizes, None) == -2
+    bad_sizes = (ctypes.c_size_t * 2)(4096, 4100)                   # not a multiple of 16
+    assert lib.moe_trans(h, dest, slots, 2, pools, groups, bad_sizes, None) == -2
+    bad_pools = (vp * 2)(0x1000, 0x2004)                            # misaligned
+    assert lib.moe_trans(h, dest, slots, 2, bad_pools, groups, sizes, None) == -2
+    missing = (vp * 2)(0x1000, 0)
+    assert lib.moe_trans(h, dest, slots, 2, missing, groups, sizes, None) == -1
+    assert lib.moe_destroy(h) == 0
+
