@@ -285,6 +285,51 @@ def main():
                              "ms_when_nothing_moves": round(ms_none, 4)}
         del pools, slots
 
+    # Receive side (Eq. 2): the rows that the other devices would send for the experts hosted here, the stand-in plan
+    # applied to every row of the gating matrix; synthetic rows, expert computation forward, then backward with the
+    # weight gradients added to those of the local pass
+    if dt == "bf16" and cfg.backward:
+        me = cfg.self_dest
+        hosted_e = wl.hosted_experts(expert_dest_np, me)
+        recv = np.zeros(cfg.G_max + 1, dtype=np.int64)
+        for j in range(cfg.P):
+            if j != me:
+                dest_j = wl.make_plan(wl.scaled(cfg, self_dest=j), gating_np[j], threshold=(cfg.index == 4))
+                for g, e in enumerate(hosted_e):
+                    recv[g + 1] += int(gating_np[j, e]) if dest_j[e] == me else 0
+        offs = np.cumsum(recv).astype(np.int32)
+        Rn = int(offs[-1])
+        if Rn > 0:
+            hr = binding.Handle(T=Rn, d=d, h=h, E=E, k=1, P=cfg.P, self_dest=me, G=cfg.G_max, dtype=dt, act=cfg.act,
+                                renorm=0, device=dev)
+            lay_r = hr.new_layout()
+            d_offs = torch.from_numpy(offs).to(dev)
+            Xr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
+            dYr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
+            Yr, dXr = torch.empty_like(Xr), torch.empty_like(Xr)
+            Zr = torch.empty(Rn, h, dtype=torch.bfloat16, device=dev)
+            Ur = torch.empty_like(Zr) if cfg.act == "swiglu" else None
+
+            def recv_pass():
+                hr.recv_layout(b.layout, d_offs, lay_r)
+                hr.expert_ffn_fwd(Xr, lay_r, W1, W2, W3, Yr, Zr, Ur)
+                hr.expert_ffn_bwd_acc(dYr, Xr, Zr, Ur, lay_r, W1, W2, W3, dXr, b.dW1, b.dW2, b.dW3)
+            recv_pass()
+            torch.cuda.synchronize()
+            re_ = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            re_[0].record()
+            for _ in range(3):
+                recv_pass()
+            re_[1].record()
+            torch.cuda.synchronize()
+            ms = re_[0].elapsed_time(re_[1]) / 3
+            fl = 3 * 2.0 * Rn * d * h * cfg.n_mats
+            per_call["recv_pass"] = {"ms": round(ms, 4), "in_step": False, "received_rows": Rn,
+                                     "rows_per_group": np.diff(offs)[:len(hosted_e)].tolist(),
+                                     "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
+                                     "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+            del Xr, dYr, Yr, dXr, Zr, Ur
+
     result = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,

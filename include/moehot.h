@@ -191,6 +191,20 @@ int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, flo
 int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const float* dlogits, const float* Wg,
                    void* dX, void* stream);
 
+/* Receive side (Eq. 2: H_i counts every input a device computes, its own and those the first all-to-all
+ * delivers for the experts it owns).  The received rows of hosted group g lie in a receive buffer at rows
+ * [recv_offsets[g], recv_offsets[g+1]); this call writes the two arrays of *out that the expert computation
+ * reads (slot_offsets[E+1], dest_slots[P+1]) so that moe_expert_ffn_fwd / _bwd run over the receive buffer with
+ * the same weight groups as over the send buffer: call them once per buffer, the second backward as
+ * moe_expert_ffn_bwd_acc so that the weight gradients of both add up.
+ *   in : local (the layout moe_dispatch wrote; dest_slots is read), recv_offsets[G+1] int32 device, non-decreasing,
+ *        constant from the number of hosted groups on
+ *   out: out->slot_offsets, out->dest_slots (the other members of *out are not touched)
+ * The handle of the receive-side calls has the same E, P, self, G, d, h, dtype and act as the local one; its
+ * T * k bounds the rows of the receive buffer. */
+int moe_recv_layout(moe_handle_t h, const moe_layout_t* local, const int32_t* recv_offsets, const moe_layout_t* out,
+                    void* stream);
+
 /* Trans on one GPU (Section 4.1: the parameters of a selected expert are transferred to the devices that
  * compute its inputs).  With the parameters of all E experts in pools in this GPU's memory, the transfer is
  * a gather of the hosted experts into the G group slots that moe_expert_ffn_fwd/bwd read, driven by the

@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_create", "moe_destroy", "moe_workspace_bytes", "moe_status_string", "moe_last_hip_error",
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
-    "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans",
+    "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans", "moe_recv_layout",
 ]
 
 
@@ -82,6 +82,7 @@ def load() -> ctypes.CDLL:
         lib.moe_gate_bwd_params.argtypes = [vp] * 7
         lib.moe_input_grad.argtypes = [vp] * 7
         lib.moe_trans.argtypes = [vp, vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
+        lib.moe_recv_layout.argtypes = [vp, ctypes.POINTER(_Layout), vp, ctypes.POINTER(_Layout), vp]
         lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
     return _lib
@@ -275,6 +276,11 @@ class Handle:
         self._check(self.lib.moe_trans(
             self._h, _ptr(expert_dest, torch.int32, self.E, "expert_dest"), _ptr(slot_expert, torch.int32, self.G, "slot_expert"),
             n, pa, ga, ba, _stream()), "moe_trans")
+
+    def recv_layout(self, local: Layout, recv_offsets, out: Layout):
+        self._check(self.lib.moe_recv_layout(
+            self._h, ctypes.byref(local.c), _ptr(recv_offsets, torch.int32, self.G + 1, "recv_offsets"),
+            ctypes.byref(out.c), _stream()), "moe_recv_layout")
 
     def gate_bwd_params(self, X, dlogits, dWg, dbg):
         f32 = torch.float32

@@ -283,6 +283,13 @@ int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, 
     return hip_status(e);
 }
 
+int moe_recv_layout(moe_handle_t h, const moe_layout_t* local, const int32_t* recv_offsets, const moe_layout_t* out, void* stream)
+{
+    if (!h || !local || !recv_offsets || !out) return MOE_ERR_NULL;
+    if (!local->dest_slots || !out->slot_offsets || !out->dest_slots) return MOE_ERR_NULL;
+    return hip_status(launch_recv_layout(h->s, local->dest_slots, recv_offsets, out->slot_offsets, out->dest_slots, (hipStream_t)stream));
+}
+
 int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream)
 {
     if (!cfg || !gating || !out) return MOE_ERR_NULL;

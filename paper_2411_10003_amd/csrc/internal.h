@@ -58,6 +58,8 @@ hipError_t launch_gate_wgrad(const moe_shape_t& s, const void* X, const float* d
 hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* slot_expert,
                                const void* pool, void* groups, long bytes_per_expert, hipStream_t st);
 hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, int32_t* slot_expert, hipStream_t st);
+hipError_t launch_recv_layout(const moe_shape_t& s, const int32_t* local_dest_slots, const int32_t* recv_offsets,
+                              int32_t* slot_offsets, int32_t* dest_slots, hipStream_t st);
 hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
 hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
 

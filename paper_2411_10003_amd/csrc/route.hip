@@ -285,6 +285,21 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void layout_positions_kernel(
     }
 }
 
+// Layout of the rows a device receives for the experts it hosts: the same slots as the local layout, the row
+// offsets of the receive buffer instead of those of the send buffer.
+__global__ void recv_layout_kernel(const int32_t* __restrict__ local_dest_slots, const int32_t* __restrict__ recv_offsets,
+                                   int32_t* __restrict__ slot_offsets, int32_t* __restrict__ dest_slots, int E, int P, int self, int G)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const int first = local_dest_slots[self];
+    if (i <= E) {
+        int g = i - first;
+        g = g < 0 ? 0 : (g > G ? G : g);
+        slot_offsets[i] = recv_offsets[g];
+    }
+    if (i <= P) dest_slots[i] = local_dest_slots[i];
+}
+
 }  // namespace
 
 hipError_t launch_chunk_hist(const moe_shape_t& s, const int32_t* idx, int32_t* chunk_hist, int n_chunks, hipStream_t st)
@@ -338,6 +353,15 @@ hipError_t launch_layout_positions(const moe_shape_t& s, const int32_t* idx, con
     hipLaunchKernelGGL(layout_positions_kernel, dim3(grid), dim3(ROUTE_WAVES * 64), 0, st, idx, expert_dest, counts, chunk_hist,
                        L.slot_of_expert, L.slot_offsets, L.dest_offsets, L.dest_slots, status, L.pos, L.perm,
                        s.T * s.k, s.E, s.P, s.self, s.G, n_chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_recv_layout(const moe_shape_t& s, const int32_t* local_dest_slots, const int32_t* recv_offsets,
+                              int32_t* slot_offsets, int32_t* dest_slots, hipStream_t st)
+{
+    const int n = (s.E > s.P ? s.E : s.P) + 1;
+    hipLaunchKernelGGL(recv_layout_kernel, dim3((n + 255) / 256), dim3(256), 0, st, local_dest_slots, recv_offsets,
+                       slot_offsets, dest_slots, s.E, s.P, s.self, s.G);
     return hipGetLastError();
 }
 
