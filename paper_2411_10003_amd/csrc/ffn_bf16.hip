@@ -172,16 +172,18 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 
     // ---- which tiles.  The kernel is persistent: one block per CU walks its share of the tiles, so a
     // tile's stores drain under the next tile's loads and nothing is relaunched.  Blocks go round-robin
-    // over the 8 XCDs (block b runs on XCD b % 8), each with its own L2; XCD x takes a contiguous,
-    // equally sized share of the tiles that actually exist (the counts are only known here) and its
-    // blocks walk it side by side in bands of 8 row tiles, column by column, so that the tiles in
-    // flight on an XCD share operand slices.
+    // over the 8 XCDs (block b runs on XCD b % 8), each with its own L2.  The tiles that actually exist
+    // (the counts are only known here) are cut into rounds of as many tiles as an XCD has blocks, 8 row
+    // tiles by 4 column tiles walked column by column inside a band of 8 row tiles, so that the tiles in
+    // flight on an XCD share operand slices in its L2; consecutive rounds go to the 8 XCDs in turn, so
+    // that at any time the XCDs work on neighbouring rounds and what one of them has fetched from HBM
+    // the others find in the memory-side cache.
     const int xcd = blockIdx.x & 7, q0 = blockIdx.x >> 3, q_stride = gridDim.x >> 3;
     const int tiles_g = p.row_tiles * p.col_tiles;         // TN: tiles of one group
-    const int cg = (tiles_g + 7) >> 3;                     // TN: an eighth of them per XCD
     const int n_act = total_rt * p.col_tiles;              // NN/NT: tiles that exist
-    const int per = (n_act + 7) >> 3;
-    const int q_end = (KIND == KIND_TN) ? p.Gcap * cg : per;
+    const int rpg = (tiles_g + q_stride - 1) / q_stride;   // TN: rounds per group
+    const int n_rounds = (KIND == KIND_TN) ? p.Gcap * rpg : (n_act + q_stride - 1) / q_stride;
+    const int q_end = ((n_rounds + 7) >> 3) * q_stride;
 
   for (int q = q0; q < q_end; q += q_stride) {
     int g, rt, ct;
@@ -189,10 +191,12 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     int k_tiles;
     int m0;                      // first output row of the tile (global row for NN/NT, row of dW for TN)
     if (KIND == KIND_TN) {
-        // every group has the same tile grid but its own contraction length: each XCD takes an
-        // eighth of every group's tiles, so the work per XCD is balanced whatever the group sizes
-        g = q / cg;
-        const int t = xcd * cg + (q - g * cg);
+        // every group has the same tile grid but its own contraction length: a round never mixes
+        // groups, so the blocks of an XCD stay on the same contraction slices of shared operands
+        const int R = ((q - q0) / q_stride) * 8 + xcd;
+        g = R / rpg;
+        if (g >= p.Gcap) break;
+        const int t = (R - g * rpg) * q_stride + q0;
         if (t >= tiles_g) continue;
         const int band = t / (BAND * p.col_tiles);
         const int in_band = t - band * BAND * p.col_tiles;
@@ -205,7 +209,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         k_tiles = (rows + BK - 1) / BK;
         m0 = rt * BM;
     } else {
-        const int t = xcd * per + q;
+        const int t = (((q - q0) / q_stride) * 8 + xcd) * q_stride + q0;
         if (t >= n_act) break;
         const int band = t / (BAND * p.col_tiles);
         const int in_band = t - band * BAND * p.col_tiles;
@@ -598,6 +602,7 @@ GemmParams base_params(const moe_shape_t& s, const ffn_args& a)
 }
 
 }  // namespace
+
 
 
 hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStream_t st)
