@@ -27,7 +27,7 @@ PEAK_F32_TFLOPS = 157.3        # fp32 vector
 PEAK_HBM_GBS = 8000.0          # HBM3E
 # HBM-side bytes of all grouped_gemm_kernel launches of one step, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
 # plain copy of known size (profiles/grouped_gemm_cfg3_pmc_traffic.txt); counters cannot be read from inside this run.
-MEASURED_FFN_TRAFFIC_BYTES = {3: 1.179e11}
+MEASURED_FFN_TRAFFIC_BYTES = {3: 1.040e11}
 
 
 def log(*a):
@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--iteration", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=0)
+    ap.add_argument("--step-only", action="store_true",
+                    help="skip the calls timed beside the step (planner, gate gradients, parameter transfer, receive-side pass): "
+                         "for profiler runs, so that per-kernel averages cover the step's launches only")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) to scale rocprofv3 FETCH_SIZE/WRITE_SIZE readings")
     args = ap.parse_args()
@@ -216,119 +219,120 @@ def main():
             e.update({"TFLOP/s": round(2 * fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
         per_call[c] = e
 
-    # the planner (Algorithm 1) on the P x E count matrix of this batch: not one of the timed calls of a step
-    # (the paper runs it under the all-to-all of the previous iteration), reported beside them
-    gating_np = wl.make_gating(cfg, counts, args.iteration)
-    gating = torch.from_numpy(gating_np).to(dev)
-    pc = wl.planner_constants(cfg)
-    pbuf = binding.PlanBuffers(cfg.P, cfg.E, dev)
-    plan_args = dict(n=1, overlap=False, alpha=1.0, **pc)
-    binding.plan(gating, pbuf, **plan_args)
-    torch.cuda.synchronize()
-    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    pe[0].record()
-    for _ in range(20):
+    if not args.step_only:
+        # the planner (Algorithm 1) on the P x E count matrix of this batch: not one of the timed calls of a step
+        # (the paper runs it under the all-to-all of the previous iteration), reported beside them
+        gating_np = wl.make_gating(cfg, counts, args.iteration)
+        gating = torch.from_numpy(gating_np).to(dev)
+        pc = wl.planner_constants(cfg)
+        pbuf = binding.PlanBuffers(cfg.P, cfg.E, dev)
+        plan_args = dict(n=1, overlap=False, alpha=1.0, **pc)
         binding.plan(gating, pbuf, **plan_args)
-    pe[1].record()
-    torch.cuda.synchronize()
-    info = pbuf.info.cpu().numpy()
-    ptimes = pbuf.times.cpu().numpy()
-    per_call["plan"] = {"ms": round(pe[0].elapsed_time(pe[1]) / 20, 4), "in_step": False, "selected": int(info[1]),
-                        "kept": int(info[0]), "model_T_before_s": float(ptimes[0]), "model_T_after_s": float(ptimes[1]),
-                        "gating": f"{cfg.P}x{cfg.E} counts, n=1, Eq. 7"}
-    if not args.no_cpu_baseline:
-        from oracle import planner_oracle as po
-        t0 = time.perf_counter()
-        ref = po.greedy_search(gating_np.astype(np.int64), 1, po.PlannerModel(alpha=1.0, overlap=False, **pc))
-        per_call["plan"]["oracle_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
-        assert ref["cnt"] == int(info[0]) and ref["T_output"] == float(ptimes[1]), "planner disagrees with its oracle"
+        torch.cuda.synchronize()
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        pe[0].record()
+        for _ in range(20):
+            binding.plan(gating, pbuf, **plan_args)
+        pe[1].record()
+        torch.cuda.synchronize()
+        info = pbuf.info.cpu().numpy()
+        ptimes = pbuf.times.cpu().numpy()
+        per_call["plan"] = {"ms": round(pe[0].elapsed_time(pe[1]) / 20, 4), "in_step": False, "selected": int(info[1]),
+                            "kept": int(info[0]), "model_T_before_s": float(ptimes[0]), "model_T_after_s": float(ptimes[1]),
+                            "gating": f"{cfg.P}x{cfg.E} counts, n=1, Eq. 7"}
+        if not args.no_cpu_baseline:
+            from oracle import planner_oracle as po
+            t0 = time.perf_counter()
+            ref = po.greedy_search(gating_np.astype(np.int64), 1, po.PlannerModel(alpha=1.0, overlap=False, **pc))
+            per_call["plan"]["oracle_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+            assert ref["cnt"] == int(info[0]) and ref["T_output"] == float(ptimes[1]), "planner disagrees with its oracle"
 
-    # the rest of the gate's backward (parameter gradients, gate path of the input gradient): beside the step
-    if cfg.backward and E <= 64:
-        dWg = torch.empty(d, E, dtype=torch.float32, device=dev)
-        dbg = torch.empty(E, dtype=torch.float32, device=dev)
-        extra = {
-            "gate_bwd_params": (lambda: hd.gate_bwd_params(X, b.dlogits, dWg, dbg), T * d * es + T * E * 4),
-            "input_grad": (lambda: hd.input_grad(b.dXp, b.layout.pos, b.dlogits, Wg, b.dX), (1 + k) * T * d * es + T * E * 4),
-        }
-        for name, (fn, nbytes) in extra.items():
-            fn()
-            torch.cuda.synchronize()
-            ee = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            ee[0].record()
-            for _ in range(10):
+        # the rest of the gate's backward (parameter gradients, gate path of the input gradient): beside the step
+        if cfg.backward and E <= 64:
+            dWg = torch.empty(d, E, dtype=torch.float32, device=dev)
+            dbg = torch.empty(E, dtype=torch.float32, device=dev)
+            extra = {
+                "gate_bwd_params": (lambda: hd.gate_bwd_params(X, b.dlogits, dWg, dbg), T * d * es + T * E * 4),
+                "input_grad": (lambda: hd.input_grad(b.dXp, b.layout.pos, b.dlogits, Wg, b.dX), (1 + k) * T * d * es + T * E * 4),
+            }
+            for name, (fn, nbytes) in extra.items():
                 fn()
-            ee[1].record()
+                torch.cuda.synchronize()
+                ee = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                ee[0].record()
+                for _ in range(10):
+                    fn()
+                ee[1].record()
+                torch.cuda.synchronize()
+                ms = ee[0].elapsed_time(ee[1]) / 10
+                per_call[name] = {"ms": round(ms, 4), "in_step": False, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                  "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
+        # Trans on one GPU: gather the hosted experts' parameters from a pool of all experts into the group slots
+        # (worst case: every slot changes; a slot that already holds its expert is skipped)
+        if dt == "bf16":
+            n_t = cfg.n_mats
+            pools = [torch.empty(E, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
+            slots = [torch.empty(cfg.G_max, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
+            slot_expert = torch.full((cfg.G_max,), -1, dtype=torch.int32, device=dev)
+            hd.trans(expert_dest, slot_expert, pools, slots)
             torch.cuda.synchronize()
-            ms = ee[0].elapsed_time(ee[1]) / 10
-            per_call[name] = {"ms": round(ms, 4), "in_step": False, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                              "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-
-    # Trans on one GPU: gather the hosted experts' parameters from a pool of all experts into the group slots
-    # (worst case: every slot changes; a slot that already holds its expert is skipped)
-    if dt == "bf16":
-        n_t = cfg.n_mats
-        pools = [torch.empty(E, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
-        slots = [torch.empty(cfg.G_max, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
-        slot_expert = torch.full((cfg.G_max,), -1, dtype=torch.int32, device=dev)
-        hd.trans(expert_dest, slot_expert, pools, slots)
-        torch.cuda.synchronize()
-        te = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        slot_expert.fill_(-1)
-        te[0].record(); hd.trans(expert_dest, slot_expert, pools, slots); te[1].record()
-        hd.trans(expert_dest, slot_expert, pools, slots); te[2].record()          # nothing to move the second time
-        torch.cuda.synchronize()
-        moved = 2.0 * len(group_rows) * n_t * d * h * es
-        ms_all, ms_none = te[0].elapsed_time(te[1]), te[1].elapsed_time(te[2])
-        per_call["trans"] = {"ms": round(ms_all, 4), "in_step": False, "GB/s": round(moved / (ms_all * 1e-3) / 1e9, 1),
-                             "hbm_frac": round(moved / (ms_all * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                             "ms_when_nothing_moves": round(ms_none, 4)}
-        del pools, slots
-
-    # Receive side (Eq. 2): the rows that the other devices would send for the experts hosted here, the stand-in plan
-    # applied to every row of the gating matrix; synthetic rows, expert computation forward, then backward with the
-    # weight gradients added to those of the local pass
-    if dt == "bf16" and cfg.backward:
-        me = cfg.self_dest
-        hosted_e = wl.hosted_experts(expert_dest_np, me)
-        recv = np.zeros(cfg.G_max + 1, dtype=np.int64)
-        for j in range(cfg.P):
-            if j != me:
-                dest_j = wl.make_plan(wl.scaled(cfg, self_dest=j), gating_np[j], threshold=(cfg.index == 4))
-                for g, e in enumerate(hosted_e):
-                    recv[g + 1] += int(gating_np[j, e]) if dest_j[e] == me else 0
-        offs = np.cumsum(recv).astype(np.int32)
-        Rn = int(offs[-1])
-        if Rn > 0:
-            hr = binding.Handle(T=Rn, d=d, h=h, E=E, k=1, P=cfg.P, self_dest=me, G=cfg.G_max, dtype=dt, act=cfg.act,
-                                renorm=0, device=dev)
-            lay_r = hr.new_layout()
-            d_offs = torch.from_numpy(offs).to(dev)
-            Xr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
-            dYr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
-            Yr, dXr = torch.empty_like(Xr), torch.empty_like(Xr)
-            Zr = torch.empty(Rn, h, dtype=torch.bfloat16, device=dev)
-            Ur = torch.empty_like(Zr) if cfg.act == "swiglu" else None
-
-            def recv_pass():
-                hr.recv_layout(b.layout, d_offs, lay_r)
-                hr.expert_ffn_fwd(Xr, lay_r, W1, W2, W3, Yr, Zr, Ur)
-                hr.expert_ffn_bwd_acc(dYr, Xr, Zr, Ur, lay_r, W1, W2, W3, dXr, b.dW1, b.dW2, b.dW3)
-            recv_pass()
+            te = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            slot_expert.fill_(-1)
+            te[0].record(); hd.trans(expert_dest, slot_expert, pools, slots); te[1].record()
+            hd.trans(expert_dest, slot_expert, pools, slots); te[2].record()          # nothing to move the second time
             torch.cuda.synchronize()
-            re_ = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            re_[0].record()
-            for _ in range(3):
+            moved = 2.0 * len(group_rows) * n_t * d * h * es
+            ms_all, ms_none = te[0].elapsed_time(te[1]), te[1].elapsed_time(te[2])
+            per_call["trans"] = {"ms": round(ms_all, 4), "in_step": False, "GB/s": round(moved / (ms_all * 1e-3) / 1e9, 1),
+                                 "hbm_frac": round(moved / (ms_all * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                 "ms_when_nothing_moves": round(ms_none, 4)}
+            del pools, slots
+
+        # Receive side (Eq. 2): the rows that the other devices would send for the experts hosted here, the stand-in plan
+        # applied to every row of the gating matrix; synthetic rows, expert computation forward, then backward with the
+        # weight gradients added to those of the local pass
+        if dt == "bf16" and cfg.backward:
+            me = cfg.self_dest
+            hosted_e = wl.hosted_experts(expert_dest_np, me)
+            recv = np.zeros(cfg.G_max + 1, dtype=np.int64)
+            for j in range(cfg.P):
+                if j != me:
+                    dest_j = wl.make_plan(wl.scaled(cfg, self_dest=j), gating_np[j], threshold=(cfg.index == 4))
+                    for g, e in enumerate(hosted_e):
+                        recv[g + 1] += int(gating_np[j, e]) if dest_j[e] == me else 0
+            offs = np.cumsum(recv).astype(np.int32)
+            Rn = int(offs[-1])
+            if Rn > 0:
+                hr = binding.Handle(T=Rn, d=d, h=h, E=E, k=1, P=cfg.P, self_dest=me, G=cfg.G_max, dtype=dt, act=cfg.act,
+                                    renorm=0, device=dev)
+                lay_r = hr.new_layout()
+                d_offs = torch.from_numpy(offs).to(dev)
+                Xr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
+                dYr = torch.randn(Rn, d, dtype=torch.bfloat16, device=dev)
+                Yr, dXr = torch.empty_like(Xr), torch.empty_like(Xr)
+                Zr = torch.empty(Rn, h, dtype=torch.bfloat16, device=dev)
+                Ur = torch.empty_like(Zr) if cfg.act == "swiglu" else None
+
+                def recv_pass():
+                    hr.recv_layout(b.layout, d_offs, lay_r)
+                    hr.expert_ffn_fwd(Xr, lay_r, W1, W2, W3, Yr, Zr, Ur)
+                    hr.expert_ffn_bwd_acc(dYr, Xr, Zr, Ur, lay_r, W1, W2, W3, dXr, b.dW1, b.dW2, b.dW3)
                 recv_pass()
-            re_[1].record()
-            torch.cuda.synchronize()
-            ms = re_[0].elapsed_time(re_[1]) / 3
-            fl = 3 * 2.0 * Rn * d * h * cfg.n_mats
-            per_call["recv_pass"] = {"ms": round(ms, 4), "in_step": False, "received_rows": Rn,
-                                     "rows_per_group": np.diff(offs)[:len(hosted_e)].tolist(),
-                                     "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
-                                     "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
-            del Xr, dYr, Yr, dXr, Zr, Ur
+                torch.cuda.synchronize()
+                re_ = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                re_[0].record()
+                for _ in range(3):
+                    recv_pass()
+                re_[1].record()
+                torch.cuda.synchronize()
+                ms = re_[0].elapsed_time(re_[1]) / 3
+                fl = 3 * 2.0 * Rn * d * h * cfg.n_mats
+                per_call["recv_pass"] = {"ms": round(ms, 4), "in_step": False, "received_rows": Rn,
+                                         "rows_per_group": np.diff(offs)[:len(hosted_e)].tolist(),
+                                         "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
+                                         "mfma_frac": round(fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+                del Xr, dYr, Yr, dXr, Zr, Ur
 
     result = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
