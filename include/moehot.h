@@ -53,9 +53,9 @@ typedef enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 } moe_act_t;
  *   self   : destination id of this GPU in [0, P).
  *   G      : capacity of the hosted weight arrays (owned + replicated experts), 1 <= G <= E.
  *   renorm : 1 = the k gate weights of a token are renormalised to sum to one.
- * Limits: 1 <= k <= 8, k <= E <= 1024, 1 <= P <= E; MOE_BF16 needs d % 64 == 0, h % 64 == 0
- * and G <= 64 (hosted weight groups);
- * T*k < 2^31 / max(d, h) is not required (row offsets are 64-bit) but T*k < 2^31 is. */
+ * Limits: 1 <= k <= 8, k <= E <= 1024, 1 <= P <= E; MOE_BF16 needs d % 64 == 0, h % 64 == 0,
+ * G <= 64 (hosted weight groups) and d*h < 2^30 (one weight matrix under 2 GiB);
+ * T*k < 2^30; T*k*max(d, h) may exceed 2^31 (row offsets are 64-bit). */
 typedef struct {
     int T, d, h, E, k, P, self, G;
     moe_dtype_t dtype;

@@ -33,6 +33,7 @@ int check_shape(const moe_shape_t& s)
     if ((long long)s.T * s.k >= (1ll << 31) / 2) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_BF16 && (s.d % 64 != 0 || s.h % 64 != 0)) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_BF16 && s.G > 64) return MOE_ERR_SHAPE;      // the grouped GEMM keeps one group per lane
+    if (s.dtype == MOE_BF16 && (long long)s.d * s.h >= (1ll << 30)) return MOE_ERR_SHAPE;   // 32-bit byte offsets inside one weight matrix
     if (s.dtype == MOE_F32 && (s.d % 4 != 0)) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_F32 && (long long)s.T * s.k > 16ll * 65535) return MOE_ERR_SHAPE;
     return MOE_OK;

@@ -233,11 +233,15 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     uint32_t voffA[2], voffB[2];                           // per-lane byte offsets of this wave's two pieces
     uint32_t ldsA[2], ldsB[2];                             // LDS byte offsets of the pieces inside a stage
     uint32_t stepA, stepB;                                 // byte advance of the source per slice
+    const bf16_t *tn_baseA = nullptr, *tn_baseB = nullptr; // TN: where the current resources start, and how many
+    long tn_bytesA = 0, tn_bytesB = 0;                     // bytes of the group's rows lie behind that point
     {
         const long a_rows = a_row_end - a_row0;
         if (KIND == KIND_TN) {
-            rA[0] = rA[1] = make_rsrc(p.A[0] + a_row0 * p.lda + m0, (a_rows * p.lda - m0) * 2);
-            rB[0] = rB[1] = make_rsrc(p.B[0] + a_row0 * p.ldb + n0, (a_rows * p.ldb - n0) * 2);
+            tn_baseA = p.A[0] + a_row0 * p.lda + m0; tn_bytesA = (a_rows * p.lda - m0) * 2;
+            tn_baseB = p.B[0] + a_row0 * p.ldb + n0; tn_bytesB = (a_rows * p.ldb - n0) * 2;
+            rA[0] = rA[1] = make_rsrc(tn_baseA, tn_bytesA);
+            rB[0] = rB[1] = make_rsrc(tn_baseB, tn_bytesB);
             stepA = (uint32_t)(BK * p.lda * 2);
             stepB = (uint32_t)(BK * p.ldb * 2);
         } else {
@@ -310,6 +314,14 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         ++iss_t; ++iss_in_seg;
         soffA += stepA; soffB += stepB;
         if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
+        // TN: the offset runs over all rows of the group.  Buffer offsets are 32 bits, so the resources
+        // are moved up to the current slice long before that overflows (a group of 2^31 bytes and more).
+        if (KIND == KIND_TN && ((soffA | soffB) & 0xc0000000u)) {
+            tn_baseA += soffA / 2; tn_bytesA -= soffA; soffA = 0;
+            tn_baseB += soffB / 2; tn_bytesB -= soffB; soffB = 0;
+            rA[0] = rA[1] = make_rsrc(tn_baseA, tn_bytesA);
+            rB[0] = rB[1] = make_rsrc(tn_baseB, tn_bytesB);
+        }
     };
 
     // ---- per-lane fragment addresses inside a stage (step half 0; half 1 is a fixed distance away)
