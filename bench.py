@@ -34,6 +34,53 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class PowerSampler:
+    """Package power from the driver's hwmon files while the timed steps run (host side, a few reads per step).
+    The grouped GEMM runs at the package power cap, so its clock, and with it the attainable MFMA rate, is set by
+    energy per flop; the reading goes into the result beside the nominal-peak fraction."""
+
+    def __init__(self):
+        import glob
+        self.inp = (glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
+                    or glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average") or [None])[0]
+        cap = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+        self.cap_w = None
+        try:
+            if cap:
+                self.cap_w = int(open(cap[0]).read()) / 1e6
+        except (OSError, ValueError):
+            pass
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                self.samples.append(int(open(self.inp).read()) / 1e6)
+            except (OSError, ValueError):
+                return
+            time.sleep(0.01)
+
+    def __enter__(self):
+        if self.inp:
+            import threading
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+
+    def result(self):
+        if not self.samples:
+            return None
+        return {"mean_w": round(float(np.mean(self.samples)), 1), "max_w": round(float(np.max(self.samples)), 1),
+                "cap_w": self.cap_w, "samples": len(self.samples)}
+
+
 def cpu_baseline(cfg, inp, expert_dest, n_tokens: int, n_hidden: int):
     """The oracle as it stands on the first n_tokens tokens of the workload: the whole layer pass,
     weight gradients on n_hidden hidden units per group with their time scaled to all h."""
@@ -182,11 +229,13 @@ def main():
     n_ev = len(calls) + 1
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_ev)] for _ in range(args.steps)]
     torch.cuda.synchronize()
+    power = PowerSampler()
     t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(events[s])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    with power:
+        for s in range(args.steps):
+            step(events[s])
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
     call_ms = {c: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
@@ -344,7 +393,7 @@ def main():
         "roofline": {"bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(cfg.index),
                      "kernel": "grouped_gemm_kernel (all launches of expert_ffn_fwd/bwd in a step)",
-                     "flops_per_step": ffn_flops, "ms_per_step": ffn_ms},
+                     "flops_per_step": ffn_flops, "ms_per_step": ffn_ms, "package_power": power.result()},
         "per_call": per_call,
     }
     if not args.no_cpu_baseline:
