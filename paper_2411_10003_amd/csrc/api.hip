@@ -51,6 +51,7 @@ struct Carve {
     void* dz() const { return base + c->off_dz; }
     void* du() const { return base + c->off_du; }
     float* gate_part() const { return reinterpret_cast<float*>(base + c->off_gate_part); }
+    float* split() const { return c->s.dtype == MOE_BF16 ? reinterpret_cast<float*>(base + c->off_split) : nullptr; }
 };
 
 }  // namespace
@@ -76,6 +77,7 @@ int moe_create(moe_handle_t* out, const moe_shape_t* shape)
     c->off_dz = off;          off += ah;
     c->off_du = off;          off += (shape->act == MOE_ACT_SWIGLU) ? ah : 0;
     c->off_gate_part = off;   off += align256((size_t)gate_grad_partitions(*shape) * ((size_t)shape->d * shape->E + shape->E) * sizeof(float));
+    c->off_split = off;       off += (shape->dtype == MOE_BF16) ? align256((size_t)SPLIT_UNITS * 256 * 256 * sizeof(float)) : 0;
     c->ws_bytes = off;
     *out = c;
     return MOE_OK;
@@ -181,7 +183,7 @@ int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* L,
     ffn_args a{};
     a.Xp = Xp; a.W1 = W1; a.W2 = W2; a.W3 = W3;
     a.slot_offsets = L->slot_offsets; a.dest_slots = L->dest_slots;
-    a.Yp = Yp; a.Z = Z; a.U = U; a.Act = c.act();
+    a.Yp = Yp; a.Z = Z; a.U = U; a.Act = c.act(); a.split_ws = c.split();
     hipStream_t st = (hipStream_t)stream;
     return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_fwd_f32(h->s, a, st) : launch_ffn_fwd_bf16(h->s, a, st));
 }
@@ -215,7 +217,7 @@ static int ffn_bwd_impl(moe_handle_t h, const void* dYp, const void* Xp, const v
     a.Z = const_cast<void*>(Z); a.U = const_cast<void*>(U); a.Act = c.act();
     a.dYp = dYp; a.dXp = dXp; a.dZ = c.dz(); a.dU = c.du();
     a.dW1 = dW1; a.dW2 = dW2; a.dW3 = dW3;
-    a.accumulate = accumulate;
+    a.accumulate = accumulate; a.split_ws = c.split();
     hipStream_t st = (hipStream_t)stream;
     return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_bwd_f32(h->s, a, st) : launch_ffn_bwd_bf16(h->s, a, st));
 }

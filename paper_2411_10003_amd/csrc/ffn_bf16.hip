@@ -54,6 +54,8 @@ struct GemmParams {
     int accumulate;              // EPI_F32: add to the output instead of overwriting it
     long ldo, o_group_stride;
     const bf16_t *Zin, *Uin;     // BWD1: saved pre-activations
+    float* split_ws;             // NN/NT: partial tiles of the K-split last round, [unit][wave][128 registers][64 lanes]
+    int split_cap;               // units that fit there
 };
 
 __device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
@@ -137,7 +139,7 @@ __device__ __forceinline__ void dma16(rsrc_t r, uint32_t lds_base, uint32_t voff
 
 
 // ---- the kernel ---------------------------------------------------------------------------------
-template <int KIND, int EPI>
+template <int KIND, int EPI, bool FIN>
 __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 {
     constexpr bool A_KMAJOR = (KIND == KIND_TN);
@@ -182,11 +184,28 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     const int tiles_g = p.row_tiles * p.col_tiles;         // TN: tiles of one group
     const int n_act = total_rt * p.col_tiles;              // NN/NT: tiles that exist
     const int rpg = (tiles_g + q_stride - 1) / q_stride;   // TN: rounds per group
-    const int n_rounds = (KIND == KIND_TN) ? p.Gcap * rpg : (n_act + q_stride - 1) / q_stride;
-    const int q_end = ((n_rounds + 7) >> 3) * q_stride;
+    // NN/NT: the tiles left over after the last full round of the chip (fewer than there are blocks) are cut
+    // along the contraction into S parts, each an item of its own, so that the last round keeps S times as
+    // many blocks busy for 1/S of a tile's time.  A part leaves its accumulators in the workspace; a second
+    // launch (FIN) adds the parts of a tile in a fixed order and runs the tile's epilogue.
+    const int nblk = gridDim.x;
+    const int n_full = (KIND == KIND_TN) ? 0 : (n_act / nblk) * nblk, rem = n_act - n_full;
+    int S = 1;
+    if (KIND != KIND_TN && rem > 0 && p.split_ws != nullptr) {
+        S = min(4, nblk / rem);
+        S = min(S, max(1, p.n_seg * (p.Kseg / BK) / 64));   // a part is worth its 256-KB round trip from 64 slices on
+        if (rem * S > p.split_cap) S = 1;
+    }
+    if (FIN && S == 1) return;
+    const int n_items = n_full + rem * S;
+    const int n_rounds = (KIND == KIND_TN) ? p.Gcap * rpg : (n_items + q_stride - 1) / q_stride;
+    const int q_first = FIN ? (int)blockIdx.x : q0;
+    const int q_step = FIN ? nblk : q_stride;
+    const int q_end = FIN ? rem : ((n_rounds + 7) >> 3) * q_stride;
 
-  for (int q = q0; q < q_end; q += q_stride) {
+  for (int q = q_first; q < q_end; q += q_step) {
     int g, rt, ct;
+    int part = 0, parts = 1, unit = 0;                     // K-split: which part of how many, and where it is kept
     long a_row0, a_row_end;      // valid rows of the A tile (NN/NT) or of the contraction (TN)
     int k_tiles;
     int m0;                      // first output row of the tile (global row for NN/NT, row of dW for TN)
@@ -209,8 +228,15 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         k_tiles = (rows + BK - 1) / BK;
         m0 = rt * BM;
     } else {
-        const int t = (((q - q0) / q_stride) * 8 + xcd) * q_stride + q0;
-        if (t >= n_act) break;
+        int t;
+        if (FIN) {
+            t = n_full + q; parts = S; unit = q * S;
+        } else {
+            const int item = (((q - q0) / q_stride) * 8 + xcd) * q_stride + q0;
+            if (item >= n_items) break;
+            t = item;
+            if (item >= n_full) { t = n_full + (item - n_full) / S; part = (item - n_full) % S; parts = S; unit = item - n_full; }
+        }
         const int band = t / (BAND * p.col_tiles);
         const int in_band = t - band * BAND * p.col_tiles;
         const int band_rows = min(BAND, total_rt - band * BAND);
@@ -226,6 +252,9 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
     const int n0 = ct * (DUAL ? BN / 2 : BN);             // first output column (hidden unit for dual)
     const int k_per_seg = (KIND == KIND_TN) ? k_tiles : p.Kseg / BK;
+    // slices of this item: all of them, or one part of a split tile; none in the finishing launch
+    const int k_lo = (int)((long)part * k_tiles / parts);
+    const int k_cnt = FIN ? 0 : (int)((long)(part + 1) * k_tiles / parts) - k_lo;
 
     // ---- buffer resources: everything outside the valid rows of an operand reads as zero --------
     // Each wave moves two 1-KB pieces of the A slice and two of the B slice per contraction slice.
@@ -295,8 +324,9 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
 
     // Slices are requested strictly in order; the source offsets advance with the stream.
-    int iss_t = 0, iss_in_seg = 0, iss_seg = 0, iss_stage = 0;
-    uint32_t soffA = 0, soffB = 0;
+    int iss_t = 0, iss_stage = 0;
+    int iss_seg = (KIND == KIND_TN) ? 0 : k_lo / k_per_seg, iss_in_seg = (KIND == KIND_TN) ? 0 : k_lo - iss_seg * k_per_seg;
+    uint32_t soffA = (uint32_t)iss_in_seg * stepA, soffB = (uint32_t)iss_in_seg * stepB;
     auto issue_next = [&]() {                              // slice iss_t -> stage iss_t % STAGES
         const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
         iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
@@ -398,7 +428,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     // before the DMA requests so that a request held up by the memory system never delays them (a
     // request placed between MFMAs stalls the matrix pipe for several MFMA slots instead).
     static_assert(WGN == 4 && PIECES == 2, "the loop is written for 8 waves");
-    if (k_tiles > 0) {
+    if (!FIN && k_cnt > 0) {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         constexpr int L = STAGES - 1;                      // slices requested ahead
         constexpr int SLICE_OPS = 2 * PIECES;              // DMA instructions of one wave per slice
@@ -407,22 +437,22 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             else if (n == 1) WAIT_VMCNT(SLICE_OPS); else WAIT_VMCNT(0);
         };
         issue_next();
-        if (k_tiles > 1) issue_next();
-        if (k_tiles > 2) issue_next();
-        if (k_tiles > 3) issue_next();
-        wait_slices(min(L, k_tiles) - 1);                  // slice 0 has landed
+        if (k_cnt > 1) issue_next();
+        if (k_cnt > 2) issue_next();
+        if (k_cnt > 3) issue_next();
+        wait_slices(min(L, k_cnt) - 1);                  // slice 0 has landed
         BLOCK_BARRIER();
         if (wm == 1) BLOCK_BARRIER();
         int cur = 0;
-        for (int t = 0; t < k_tiles; ++t) {
+        for (int t = 0; t < k_cnt; ++t) {
             // fetch phase.  Ring slot (t+4) % 5 held slice t-1, which every wave finished reading at
             // least one barrier ago.
             load_frags(fa0, fb0, cur, 0);
             load_frags(fa1, fb1, cur, 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (t + L < k_tiles) issue_next();
+            if (t + L < k_cnt) issue_next();
             // this wave's pieces of slice t+1 must have landed before the barrier lets anyone read them
-            wait_slices(min(t + L, k_tiles - 1) - (t + 1));
+            wait_slices(min(t + L, k_cnt - 1) - (t + 1));
             wait_frags();
             BLOCK_BARRIER();
             // multiply phase
@@ -438,6 +468,21 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");     // the last MFMAs have written back before the accumulators are read
+    // partial tiles: [unit][wave][register / 4][lane] as float4, every instruction moves 1 KB
+    if (KIND != KIND_TN && !FIN && parts > 1) {
+        float4* ws4 = reinterpret_cast<float4*>(p.split_ws) + ((size_t)unit * NWAVES + wave) * (TM * TN * 4) * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4)
+                    ws4[((i * TN + j) * 4 + e4) * 64] = make_float4(acc[i][j][e4 * 4], acc[i][j][e4 * 4 + 1], acc[i][j][e4 * 4 + 2], acc[i][j][e4 * 4 + 3]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        __syncthreads();
+        continue;
+    }
     // ---- epilogue.  A lane holds, per fragment, row l%32 and columns q*8 + (l/32)*4 + 0..3: storing
     // from there would touch 16-byte pieces of 32 different rows per instruction.  Instead every wave
     // passes its 128 x 64 accumulators through its own LDS patch (64 rows at a time, fp32) and reads
@@ -463,8 +508,19 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const f32x16& a = acc[half * 2 + ii][j];
-                    *reinterpret_cast<float4*>(patch + (ii * 32 + lrow) * EP_PITCH + (j * 32 + q * 8 + lcol) * 4) =
-                        make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
+                    float4 val = make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
+                    if (KIND != KIND_TN && FIN) {                  // the parts of a split tile, added in ascending order
+                        const float4* ws4 = reinterpret_cast<const float4*>(p.split_ws) + ((size_t)unit * NWAVES + wave) * (TM * TN * 4) * 64 + lane;
+                        float4 v[4];                               // at most 4 parts; all loads independent of each other
+#pragma unroll
+                        for (int s = 0; s < 4; ++s)
+                            v[s] = (s < parts) ? ws4[(size_t)s * NWAVES * (TM * TN * 4) * 64 + (((half * 2 + ii) * TN + j) * 4 + q) * 64]
+                                               : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                        val = v[0];
+#pragma unroll
+                        for (int s = 1; s < 4; ++s) { val.x += v[s].x; val.y += v[s].y; val.z += v[s].z; val.w += v[s].w; }
+                    }
+                    *reinterpret_cast<float4*>(patch + (ii * 32 + lrow) * EP_PITCH + (j * 32 + q * 8 + lcol) * 4) = val;
                 }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
@@ -593,14 +649,24 @@ hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st
         cus = n / 8 * 8;
     }
     const int grid = cus;
-    auto kern = grouped_gemm_kernel<KIND, EPI>;
+    auto kern = grouped_gemm_kernel<KIND, EPI, false>;
+    auto kern_fin = grouped_gemm_kernel<KIND, EPI, KIND != KIND_TN>;     // TN has no split round
     static bool configured = false;      // per instantiation
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
+        if (e == hipSuccess && KIND != KIND_TN)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_fin), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
         if (e != hipSuccess) return e;
         configured = true;
     }
+    // short contractions gain less from the split than the second launch costs
+    if (KIND == KIND_TN || p.n_seg * (p.Kseg / BK) < 128) p.split_ws = nullptr;
+    p.split_cap = SPLIT_UNITS;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), LDS_BYTES, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || KIND == KIND_TN || p.split_ws == nullptr) return e;
+    // the tiles of a K-split last round: add their parts, run their epilogues
+    hipLaunchKernelGGL(kern_fin, dim3(grid), dim3(NT), LDS_BYTES, st, p);
     return hipGetLastError();
 }
 
@@ -610,6 +676,7 @@ GemmParams base_params(const moe_shape_t& s, const ffn_args& a)
     p.slot_offsets = a.slot_offsets; p.dest_slots = a.dest_slots;
     p.self = s.self; p.Gcap = s.G;
     p.n_seg = 1;
+    p.split_ws = a.split_ws;
     return p;
 }
 

@@ -17,6 +17,7 @@ struct moe_ctx {
     size_t off_dz;         // elt [A,h]  dZ
     size_t off_du;         // elt [A,h]  dU (SwiGLU)
     size_t off_gate_part;  // float [partitions][d*E + E] partial sums of the gate parameter gradients
+    size_t off_split;      // float [SPLIT_UNITS][256*256] partial tiles of the grouped GEMM's last, K-split round (bf16 path)
     size_t ws_bytes;
     int n_chunks;          // ceil(A / ROUTE_CHUNK)
     // per-chunk histograms left in a workspace by the last moe_expert_counts: whose they are
@@ -63,6 +64,7 @@ hipError_t launch_recv_layout(const moe_shape_t& s, const int32_t* local_dest_sl
 hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
 hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int32_t* pos, void* dX, hipStream_t st);
 
+constexpr int SPLIT_UNITS = 320;       // partial tiles the K-split of a last round may need: at most one per block
 struct ffn_args {
     const void *Xp, *W1, *W2, *W3;
     const int32_t *slot_offsets, *dest_slots;
@@ -71,6 +73,7 @@ struct ffn_args {
     void *dXp, *dZ, *dU;               // dZ, dU in workspace
     float *dW1, *dW2, *dW3;
     bool accumulate = false;           // weight gradients are added to what dW holds instead of overwriting it
+    float* split_ws = nullptr;         // workspace for K-split partial tiles (SPLIT_UNITS tiles of 256 x 256 floats)
 };
 hipError_t launch_ffn_fwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);
 hipError_t launch_ffn_bwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);

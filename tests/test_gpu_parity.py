@@ -145,6 +145,10 @@ FFN_CASES = [
     _cfg(1, T=1100, d=128, h=320, backward=True),                         # bf16 GELU, ragged tiles
     _cfg(3, T=900, d=192, h=256, backward=True),                          # bf16 SwiGLU
     _cfg(4, T=2000, d=128, h=128, backward=True),                         # 64 experts, k = 1, tiny groups
+    # contractions of 128 slices and more: the few tiles there are get split along the contraction (two to four
+    # parts, over both segments of the SwiGLU input gradient) and are finished by the second launch
+    _cfg(3, T=500, d=128, h=4096, backward=True),
+    _cfg(1, T=600, d=4096, h=128, backward=True),
 ]
 
 
