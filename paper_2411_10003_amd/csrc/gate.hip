@@ -267,28 +267,55 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_topk_fast_kernel(
         else asm volatile("s_waitcnt vmcnt(%0)" :: "n"(W_PIECES) : "memory");
         asm volatile("s_barrier" ::: "memory");
         if (c + 2 < n_chunks) issue(c + 2);
-        const unsigned char* st = gsm + (c % NST) * STAGE;
-        const bf16_t* xs = reinterpret_cast<const bf16_t*>(st + W_BYTES) + (size_t)wave * TOK * RC;
+        // The reads of a 64-column step (TOK token values of the lane's column, the E weights of its row) are
+        // issued together, one step ahead of the multiply-adds that use them, and waited for once: left to the
+        // compiler every read is followed by a wait of its own.
+        const uint32_t st = lds0 + (uint32_t)(c % NST) * STAGE;
+        const uint32_t xa0 = st + W_BYTES + (uint32_t)((wave * TOK * RC + lane) * 2);
+        typedef __attribute__((ext_vector_type(4))) float gate_f4;
+        uint32_t xr[2][TOK];
+        gate_f4 wr[2][E4];
+        auto request = [&](int js, uint32_t (&xq)[TOK], gate_f4 (&wq)[E4]) {
+            const uint32_t xa = xa0 + (uint32_t)js * 128;
 #pragma unroll
-        for (int js = 0; js < RC / 64; ++js) {
-            float x[TOK];
-#pragma unroll
-            for (int tk = 0; tk < TOK; ++tk) x[tk] = bf16_to_f32(xs[tk * RC + js * 64 + lane]);
+            for (int tk = 0; tk < TOK; ++tk)
+                asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(xq[tk]) : "v"(xa), "n"(tk * RC * 2));
             const int r = js * 64 + lane;
-            const float4* wrow = reinterpret_cast<const float4*>(st) + r * E4;
             const int sw = (r >> SW_SHIFT) & (E4 - 1);
 #pragma unroll
             for (int e4 = 0; e4 < E4; ++e4) {
-                const float4 wv = wrow[e4 ^ sw];
+                const uint32_t wa = st + (uint32_t)((r * E4 + (e4 ^ sw)) * 16);
+                asm volatile("ds_read_b128 %0, %1" : "=v"(wq[e4]) : "v"(wa));
+            }
+        };
+        auto arrive = [&](uint32_t (&xq)[TOK], gate_f4 (&wq)[E4]) {            // everything requested so far has landed
+#pragma unroll
+            for (int tk = 0; tk < TOK; ++tk) asm volatile("" : "+v"(xq[tk]));
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int tk = 0; tk < TOK; ++tk) asm volatile("" : "+v"(xq[tk]));
+#pragma unroll
+            for (int e4 = 0; e4 < E4; ++e4) asm volatile("" : "+v"(wq[e4]));
+        };
+        auto multiply = [&](const uint32_t (&xq)[TOK], const gate_f4 (&wq)[E4]) {
+#pragma unroll
+            for (int e4 = 0; e4 < E4; ++e4)
 #pragma unroll
                 for (int tk = 0; tk < TOK; ++tk) {
+                    const float x = __uint_as_float(xq[tk] << 16);
                     float* a = &acc[tk * EC + e4 * 4];
-                    a[0] = fmaf(x[tk], wv.x, a[0]);
-                    a[1] = fmaf(x[tk], wv.y, a[1]);
-                    a[2] = fmaf(x[tk], wv.z, a[2]);
-                    a[3] = fmaf(x[tk], wv.w, a[3]);
+                    a[0] = fmaf(x, wq[e4][0], a[0]);
+                    a[1] = fmaf(x, wq[e4][1], a[1]);
+                    a[2] = fmaf(x, wq[e4][2], a[2]);
+                    a[3] = fmaf(x, wq[e4][3], a[3]);
                 }
-            }
+        };
+        request(0, xr[0], wr[0]);
+#pragma unroll
+        for (int js = 0; js < RC / 64; ++js) {
+            arrive(xr[js & 1], wr[js & 1]);
+            if (js + 1 < RC / 64) request(js + 1, xr[(js + 1) & 1], wr[(js + 1) & 1]);
+            multiply(xr[js & 1], wr[js & 1]);
         }
     }
     fold_and_store<EC>(acc, lane, wave, tok0, 0, T, E, e_pitch, bg, logit_lds, logits);
