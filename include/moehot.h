@@ -102,8 +102,9 @@ int moe_read_status(moe_handle_t h, const void* ws, void* stream, int* status);
 
 /* Gate and routing (Section 2.1: the gate relates an input to all experts and routes it to the
  * top-k).  logits[t,e] = bg[e] + sum_c X[t,c] * Wg[c,e] in fp32 with a fixed summation order
- * (64 column-strided partial sums built with fused multiply-adds, folded by halving offsets, bias
- * last) so that routing is reproducible bit for bit.  idx[t,0..k) = the k largest logits, best
+ * (two partial sums fed by alternating blocks of 32 columns; inside a block the columns are visited
+ * as 8q + j, j = 0..7 outer, q = 0..3 inner, one fused multiply-add each; logit = (s0 + s1) + bias:
+ * the order of the fp32 matrix instruction) so that routing is reproducible bit for bit.  idx[t,0..k) = the k largest logits, best
  * first, ties to the lowest index, NaN ranked as -inf.  p = softmax(logits[t,:]);
  * w[t,j] = p[idx[t,j]], divided by their sum over j when renorm = 1.
  *   in : X[T,d] elt, Wg[d,E] float, bg[E] float

@@ -38,23 +38,24 @@
 /* ---------------------------------------------------------------------------------------
  * Gate logits (Section 2.1: "computes the relationship between that input and all the
  * experts"), read as logit[t,e] = b[e] + sum_c X[t,c] * Wg[c,e] in fp32 with this order:
- * 64 partial sums, partial l takes columns c = l, l+64, l+128, ... ascending, each step one
- * fused multiply-add; the partials are then folded pairwise l <- l + (l+off) for
- * off = 32,16,8,4,2,1; the bias is added last.
+ * two partial sums; the columns are taken in blocks of 32, block B (columns 32B .. 32B+31)
+ * belongs to partial B mod 2; inside a block the columns are visited as c = 32B + 8q + j with
+ * j = 0..7 in the outer and q = 0..3 in the inner loop, each step one fused multiply-add
+ * onto the partial; logit = (s0 + s1) + b[e].  Denormals are kept.
  */
 void orc_gate_logits(const float* X, const float* Wg, const float* bg, int T, int d, int E, float* logits)
 {
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < T; ++t) {
         for (int e = 0; e < E; ++e) {
-            float s[64];
-            for (int l = 0; l < 64; ++l) s[l] = 0.0f;
-            for (int c0 = 0; c0 < d; c0 += 64)
-                for (int l = 0; l < 64 && c0 + l < d; ++l)
-                    s[l] = fmaf(X[(size_t)t * d + c0 + l], Wg[(size_t)(c0 + l) * E + e], s[l]);
-            for (int off = 32; off >= 1; off >>= 1)
-                for (int l = 0; l < off; ++l) s[l] = s[l] + s[l + off];
-            logits[(size_t)t * E + e] = s[0] + bg[e];
+            float s[2] = {0.0f, 0.0f};
+            for (int B = 0; 32 * B < d; ++B)
+                for (int j = 0; j < 8; ++j)
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = 32 * B + 8 * q + j;
+                        if (c < d) s[B & 1] = fmaf(X[(size_t)t * d + c], Wg[(size_t)c * E + e], s[B & 1]);
+                    }
+            logits[(size_t)t * E + e] = (s[0] + s[1]) + bg[e];
         }
     }
 }

@@ -27,16 +27,24 @@ def _cfg(ci, **kw):
     return wl.scaled(wl.CONFIGS[ci], **kw)
 
 
-# shapes chosen to span several tiles and ragged tails: T not a multiple of 64 or of the
-# tokens-per-block, d with several 64-column steps, E above 64 (two expert passes), k up to 3
+# shapes chosen to span several tiles and ragged tails: T not a multiple of the 64 tokens of a block, d with
+# one, two and many 64-column chunks (fewer than, as many as and several times the chunks requested ahead),
+# E below, at and above a multiple of 16, E above 64 (several expert passes), k up to 3
 GATE_CASES = [
     _cfg(0),                                                  # the tiny fp32 configuration, complete
     _cfg(0, T=333, d=100, E=8, k=1, P=4),                     # fp32, column tail (d % 64 != 0)
+    _cfg(0, T=200, d=1024, E=16, k=2, P=4),                   # fp32 tokens, whole chunks
     _cfg(1, T=1000, d=320, h=64),
-    _cfg(1, T=1001, d=512, h=64),                             # E = 16 fast path (LDS-streamed), ragged last block
+    _cfg(1, T=1001, d=512, h=64),                             # exactly the chunks requested ahead, ragged last block
+    _cfg(1, T=130, d=64, h=64),                               # one chunk
+    _cfg(1, T=130, d=128, h=64),                              # two chunks
+    _cfg(1, T=640, d=4096, h=64),                             # the long rows of the largest configuration
     _cfg(2, T=777, d=256, h=64, E=32, k=2),
+    _cfg(2, T=640, d=2048, h=64, E=32, k=2),
     _cfg(4, T=515, d=192, h=64, E=64, k=1, P=16),
+    _cfg(4, T=640, d=2048, h=64, E=64, k=1, P=16),
     _cfg(1, T=300, d=128, h=64, E=100, k=3, P=10, n_replicas=1),
+    _cfg(1, T=300, d=1024, h=64, E=128, k=2, P=8, n_replicas=1),   # two passes of 64 experts, whole chunks
     _cfg(1, T=65, d=64, h=64, E=5, k=2, P=5, n_replicas=1),
 ]
 

@@ -33,23 +33,31 @@ def _round_f32(q: Fraction) -> Fraction:
     return sign * fl * Fraction(2) ** e
 
 
+def _column_order(d):
+    """(block, column) in the order of the reading: blocks of 32 columns; position n of a block is
+    its column 8 * (n % 4) + n // 4; columns at or past d are skipped."""
+    return [(blk, 32 * blk + 8 * (n % 4) + n // 4) for blk in range((d + 31) // 32) for n in range(32)
+            if 32 * blk + 8 * (n % 4) + n // 4 < d]
+
+
 def _logit_exact_order(x, wcol, b):
-    """The fixed summation order, written with rationals: 64 strided partial sums built with
-    fused multiply-adds, folded by halving offsets, bias last."""
-    d = len(x)
-    s = [Fraction(0)] * 64
-    for c in range(d):
-        l = c % 64
-        s[l] = _round_f32(Fraction(float(x[c])) * Fraction(float(wcol[c])) + s[l])
-    off = 32
-    while off >= 1:
-        for l in range(off):
-            s[l] = _round_f32(s[l] + s[l + off])
-        off //= 2
-    return _round_f32(s[0] + Fraction(float(b)))
+    """The fixed summation order, written with rationals: two partial sums fed by alternating
+    blocks of 32 columns, one fused multiply-add per column, (s0 + s1) + bias."""
+    s = [Fraction(0), Fraction(0)]
+    for blk, c in _column_order(len(x)):
+        s[blk % 2] = _round_f32(Fraction(float(x[c])) * Fraction(float(wcol[c])) + s[blk % 2])
+    return _round_f32(_round_f32(s[0] + s[1]) + Fraction(float(b)))
 
 
-@pytest.mark.parametrize("d", [64, 100, 192, 257])
+def test_column_order_is_a_permutation_with_the_stated_head():
+    order = [c for _, c in _column_order(100)]
+    assert sorted(order) == list(range(100))
+    assert order[:9] == [0, 8, 16, 24, 1, 9, 17, 25, 2]
+    assert order[32:36] == [32, 40, 48, 56]
+    assert order[-4:] == [96, 97, 98, 99]          # the last block keeps only columns below d
+
+
+@pytest.mark.parametrize("d", [24, 64, 100, 192, 257])
 def test_logits_bitwise_vs_rational_fma(orc, d):
     rng = np.random.default_rng(d)
     T, E = 3, 4
