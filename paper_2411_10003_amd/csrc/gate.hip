@@ -18,6 +18,7 @@ constexpr int GATE_THREADS = GATE_WAVES * 64;
 constexpr int GATE_TOK = GATE_WAVES * 16;     // tokens per block
 
 typedef float gate_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned gate_u4 __attribute__((ext_vector_type(4)));
 
 // Eight consecutive columns of one token, as loaded.
 template <typename XT> struct XPiece;
@@ -251,6 +252,155 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_mfma_kernel(
     }
 }
 
+// ---- bf16 tokens, d % 64 == 0, every staged expert exists: the same contraction with both operands delivered by
+// buffer loads that write LDS directly, so that nothing asynchronous ever targets a register and the waits can be
+// written by hand (the compiler's own counts allow a third of the requests that may be outstanding).
+// Per wave a ring of NXP token chunks (its 16 tokens x 64 columns, 2 KB: lane l's two 16-byte pieces at l * 16);
+// per block a ring of NXP + 1 gate-matrix chunks (64 columns x 16 NT experts), every wave fetching a quarter.
+// A gate-matrix piece (4 consecutive experts of one column) lands where the instruction that uses it finds the 64
+// values of its lanes side by side: piece (block s, j, tile, q, i / 4) at 16 * ((((8 s + j) NT + tile) 4 + q) 4 + i / 4),
+// so the A operand of instruction (s, j, tile) is one `ds_read_b32` at lane * 4 plus a constant.
+typedef __attribute__((ext_vector_type(4))) int gate_rsrc_t;
+#define GATE_LDS_PTR(T) __attribute__((address_space(3))) T*
+
+__device__ __forceinline__ gate_rsrc_t gate_make_rsrc(const void* base, unsigned long long bytes)
+{
+    if (bytes > 0xffffffffull) bytes = 0xffffffffull;
+    const unsigned long long b = (unsigned long long)base;
+    gate_rsrc_t r;
+    r[0] = (int)(unsigned)(b & 0xffffffffull);
+    r[1] = (int)(unsigned)((b >> 32) & 0xffffull);
+    r[2] = (int)(unsigned)bytes;                           // reads at or past this limit return zero
+    r[3] = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void gate_dma16(gate_rsrc_t r, uint32_t lds_base, uint32_t voff, uint32_t soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(r), "s"(soff) : "memory");
+}
+
+constexpr int GATE_NXP = 5;                                // token chunks requested ahead
+constexpr int GATE_NW = GATE_NXP + 1;                      // gate-matrix chunks in the ring
+constexpr int GATE_XSLOT = 2048;                           // bytes of one wave's token chunk
+constexpr int GATE_XRING = GATE_WAVES * GATE_NXP * GATE_XSLOT;
+
+template <int NT, bool ROUTE>
+__global__ __launch_bounds__(GATE_THREADS) void gate_mfma_dma_kernel(
+    const bf16_t* __restrict__ X, const float* __restrict__ Wg, const float* __restrict__ bg,
+    float* __restrict__ logits, int32_t* __restrict__ idx, float* __restrict__ wout,
+    int T, int d, int E, int k, int renorm, int e_pitch)
+{
+    constexpr int NXP = GATE_NXP, NW = GATE_NW, XSLOT = GATE_XSLOT, XRING = GATE_XRING;
+    constexpr int WCH = 4096 * NT;                         // bytes of one gate-matrix chunk
+    constexpr int LPS = 2 + NT;                            // requests of one wave per chunk
+    extern __shared__ __attribute__((aligned(1024))) unsigned char gsm[];   // token rings | gate-matrix ring | logits
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(GATE_LDS_PTR(unsigned char))gsm;
+    float* logit_lds = reinterpret_cast<float*>(gsm + XRING + NW * WCH);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane >> 4, i16 = lane & 15;
+    const int blk_tok0 = blockIdx.x * GATE_TOK;
+    const int tok0w = blk_tok0 + wave * 16;
+    const int tok = tok0w + i16;
+    const int npairs = d / 64;
+
+    // tokens: rows of this block onwards; a token past the end reads the last one (never stored); a chunk past the
+    // end of a row reads into the next rows or, after the last row, zeros: never multiplied
+    const gate_rsrc_t rX = gate_make_rsrc(X + (size_t)blk_tok0 * d, (unsigned long long)(T - blk_tok0) * d * 2);
+    const int rowrel = (tok < T ? tok : T - 1) - blk_tok0;
+    const uint32_t xv0 = (uint32_t)((rowrel * d + 8 * q) * 2), xv1 = xv0 + 64;
+    const uint32_t xl_w = lds0 + (uint32_t)(wave * NXP * XSLOT);
+    // gate matrix: this wave's NT requests of a chunk
+    uint32_t wv[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int L = (wave * NT + n) * 64 + lane;         // 16-byte slot of the chunk
+        const int e4l = L & 3, qq = (L >> 2) & 3, tl = (L >> 4) % NT, sj = L / (16 * NT);
+        const int c_local = 32 * (sj >> 3) + 8 * qq + (sj & 7);
+        wv[n] = (uint32_t)((c_local * E + 16 * tl + 4 * e4l) * 4);
+    }
+    const uint32_t wl_w = lds0 + (uint32_t)(XRING + wave * NT * 1024);
+
+    for (int ec0 = 0; ec0 < E; ec0 += 16 * NT) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // the stores of the previous pass do not count below
+        // columns at or past d are at or past the limit: zeros
+        const gate_rsrc_t rW = gate_make_rsrc(Wg + ec0, ((unsigned long long)d * E - ec0) * 4);
+        auto issue = [&](int P, int xslot, int wstage) {
+            gate_dma16(rX, xl_w + (uint32_t)(xslot * XSLOT), xv0, (uint32_t)P * 128u);
+            gate_dma16(rX, xl_w + (uint32_t)(xslot * XSLOT + 1024), xv1, (uint32_t)P * 128u);
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+                gate_dma16(rW, wl_w + (uint32_t)(wstage * WCH + n * 1024), wv[n], (uint32_t)P * (uint32_t)(64 * E * 4));
+        };
+        gate_f4 acc[2][NT];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int tl = 0; tl < NT; ++tl) acc[s][tl] = gate_f4{0.0f, 0.0f, 0.0f, 0.0f};
+
+#pragma unroll
+        for (int P = 0; P < NXP; ++P) issue(P, P, P);
+        int xslot = 0, wstage = 0;
+        for (int p = 0; p < npairs; ++p) {
+            // this wave's requests for chunk p have landed (NXP - 1 younger groups may be pending); after the barrier
+            // so have everybody's quarters of the gate-matrix chunk, and everybody is done with chunk p - 1
+            asm volatile("s_waitcnt vmcnt(%0)" :: "n"((NXP - 1) * LPS) : "memory");
+            asm volatile("s_barrier" ::: "memory");
+            const unsigned char* xs = gsm + (wave * NXP + xslot) * XSLOT + lane * 16;
+            const gate_u4 x0 = *reinterpret_cast<const gate_u4*>(xs);
+            const gate_u4 x1 = *reinterpret_cast<const gate_u4*>(xs + 1024);
+            const float* wsb = reinterpret_cast<const float*>(gsm + XRING + wstage * WCH) + lane;
+            float wf[2][8][NT];
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int tl = 0; tl < NT; ++tl) wf[s][j][tl] = wsb[((s * 8 + j) * NT + tl) * 64];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t w0 = x0[j / 2], w1 = x1[j / 2];
+                const float a0 = __uint_as_float((j & 1) ? (w0 & 0xffff0000u) : (w0 << 16));
+                const float a1 = __uint_as_float((j & 1) ? (w1 & 0xffff0000u) : (w1 << 16));
+#pragma unroll
+                for (int tl = 0; tl < NT; ++tl) {
+                    acc[0][tl] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[0][j][tl], a0, acc[0][tl], 0, 0, 0);
+                    acc[1][tl] = __builtin_amdgcn_mfma_f32_16x16x4f32(wf[1][j][tl], a1, acc[1][tl], 0, 0, 0);
+                }
+            }
+            // the reads of this chunk have returned before its slot is requested again
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            issue(p + NXP, xslot, wstage == 0 ? NW - 1 : wstage - 1);
+            xslot = (xslot + 1 == NXP) ? 0 : xslot + 1;
+            wstage = (wstage + 1 == NW) ? 0 : wstage + 1;
+        }
+        // requests past the end are still on their way into the rings: nothing may reuse LDS before they land
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+
+        // lane l, register r of tile tl: expert ec0 + 16 tl + 4q + r, token i16
+#pragma unroll
+        for (int tl = 0; tl < NT; ++tl)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int e = ec0 + 16 * tl + 4 * q + r;
+                const float v = (acc[0][tl][r] + acc[1][tl][r]) + bg[e];
+                if (ROUTE) logit_lds[(wave * 16 + i16) * e_pitch + e] = v;
+                else if (tok < T) logits[(size_t)tok * E + e] = v;
+            }
+    }
+    if (ROUTE) {
+        __syncthreads();
+        for (int i = lane; i < 16 * E; i += 64) {                 // the wave's 16 rows of logits are contiguous
+            const int tk = i / E, e = i - tk * E;
+            if (tok0w + tk < T) logits[(size_t)tok0w * E + i] = logit_lds[(wave * 16 + tk) * e_pitch + e];
+        }
+        if (lane < 16 && tok < T) route_one(logit_lds + (wave * 16 + lane) * e_pitch, tok, E, k, renorm, idx, wout);
+    }
+}
+
 // Routing from logits in global memory (E > 64: the logits were written in passes).
 __global__ void gate_route_kernel(const float* __restrict__ logits, int32_t* __restrict__ idx, float* __restrict__ wout,
                                   int T, int E, int k, int renorm)
@@ -318,6 +468,37 @@ hipError_t run_gate(const moe_shape_t& s, const void* X, const float* Wg, const 
     return hipGetLastError();
 }
 
+template <int NT>
+hipError_t run_gate_dma(const moe_shape_t& s, const void* X, const float* Wg, const float* bg,
+                        float* logits, int32_t* idx, float* w, hipStream_t st)
+{
+    const int grid = (s.T + GATE_TOK - 1) / GATE_TOK;
+    const bool route = s.E <= 16 * NT;
+    const int e_pitch = s.E | 1;
+    const size_t lds = (size_t)GATE_XRING + (size_t)GATE_NW * 4096 * NT + (route ? (size_t)GATE_TOK * e_pitch * sizeof(float) : 0);
+    auto kr = gate_mfma_dma_kernel<NT, true>;
+    auto kn = gate_mfma_dma_kernel<NT, false>;
+    static bool configured = false;
+    if (!configured) {
+        const int most = GATE_XRING + GATE_NW * 4096 * NT + GATE_TOK * (16 * NT + 1) * (int)sizeof(float);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kr), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kn), hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    if (route) {
+        hipLaunchKernelGGL(kr, dim3(grid), dim3(GATE_THREADS), lds, st, (const bf16_t*)X, Wg, bg, logits, idx, w,
+                           s.T, s.d, s.E, s.k, s.renorm, e_pitch);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(kn, dim3(grid), dim3(GATE_THREADS), lds, st, (const bf16_t*)X, Wg, bg, logits, idx, w,
+                       s.T, s.d, s.E, s.k, s.renorm, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(gate_route_kernel, dim3((s.T + 255) / 256), dim3(256), 0, st, logits, idx, w, s.T, s.E, s.k, s.renorm);
+    return hipGetLastError();
+}
+
 template <typename XT, int NT, int NXP>
 hipError_t run_gate_n(const moe_shape_t& s, const void* X, const float* Wg, const float* bg,
                       float* logits, int32_t* idx, float* w, hipStream_t st)
@@ -346,6 +527,12 @@ hipError_t launch_gate_topk(const moe_shape_t& s, const void* X, const float* Wg
 {
     if (s.T == 0) return hipSuccess;
     if (s.dtype == MOE_F32) return run_gate_t<float>(s, X, Wg, bg, logits, idx, w, st);
+    // rows of 64 tokens must stay inside the 32-bit offsets of a buffer load
+    if (s.d % 64 == 0 && (long long)s.d * 2 * (GATE_TOK + 1) < (1ll << 31) && (long long)s.d * s.E * 4 < (1ll << 31)) {
+        if (s.E == 16) return run_gate_dma<1>(s, X, Wg, bg, logits, idx, w, st);
+        if (s.E == 32) return run_gate_dma<2>(s, X, Wg, bg, logits, idx, w, st);
+        if (s.E % 64 == 0) return run_gate_dma<4>(s, X, Wg, bg, logits, idx, w, st);
+    }
     return run_gate_t<bf16_t>(s, X, Wg, bg, logits, idx, w, st);
 }
 
