@@ -76,6 +76,35 @@ def test_gate_exact_ties_go_to_lowest_index(G):
     assert np.allclose(G.host(b.w), 0.5, rtol=1e-6)
 
 
+@pytest.mark.parametrize("cfg", [_cfg(1, T=200, d=256, h=64), _cfg(0, T=200, d=100, E=8, k=2, P=4)],
+                         ids=lambda c: f"{c.dtype}-d{c.d}-E{c.E}")
+def test_gate_with_infinities_and_nans(G, orc, cfg):
+    """Non-finite inputs take the IEEE route on both sides: an infinite token value or bias gives an infinite
+    or NaN logit, NaN ranks as -inf in the selection, and the other tokens are untouched."""
+    case = G.Case(cfg)
+    X, Wg, bg = case.inp["X"].copy(), case.inp["Wg"].copy(), case.inp["bg"].copy()
+    X[3, 5] = np.inf                      # logits of token 3: +-inf by the sign of Wg[5, e]
+    X[7, 0] = np.nan                      # all logits of token 7 are NaN
+    X[11, 17] = -np.inf
+    X[11, 18] = np.inf                    # inf - inf somewhere along the chains of token 11
+    bg[2] = -np.inf                       # expert 2 is never chosen by a finite token
+    ref = orc.route(X, Wg, bg, cfg.k, cfg.renorm)
+    hd = G.make_handle(cfg)
+    b = G.binding.LayerBuffers(hd, False)
+    hd.gate_topk(G.dev(X, cfg.dtype), G.dev(Wg), G.dev(bg), b.logits, b.idx, b.w)
+    torch.cuda.synchronize()
+    got = G.host(b.logits)
+    both_nan = np.isnan(got) & np.isnan(ref["logits"])
+    assert np.array_equal(np.isnan(got), np.isnan(ref["logits"]))
+    assert np.array_equal(got.view(np.uint32)[~both_nan], ref["logits"].view(np.uint32)[~both_nan])
+    assert np.isnan(got[7]).all() and np.isinf(got[3]).any() and (got[:, 2][~np.isnan(got[:, 2])] == -np.inf).all()
+    assert np.array_equal(G.host(b.idx), ref["idx"])
+    finite = np.isfinite(ref["w"]).all(axis=1)
+    assert finite.sum() >= cfg.T - 3
+    assert np.allclose(G.host(b.w)[finite], ref["w"][finite], rtol=1e-5, atol=1e-7)
+    assert not (G.host(b.idx)[finite] == 2).any()
+
+
 PLANS = ["planner", "all_owner", "all_self", "round_robin", "self_last"]
 
 
