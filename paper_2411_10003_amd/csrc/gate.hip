@@ -105,6 +105,53 @@ __device__ __forceinline__ void route_one(const float* lg, int t, int E, int k, 
     }
 }
 
+// The same routing by four lanes per token (lane = 4 * token + part; part takes the experts e = part, part + 4, ...):
+// every lane proposes its best remaining logit, two exchange steps pick the winner by (value descending, index
+// ascending), which is the order of the serial scan; the softmax sum is folded the same way.  All 64 lanes take part
+// in the exchanges; `store` says whether the token exists.
+__device__ __forceinline__ void route_four(const float* lg, int part, int t, bool store, int E, int k, int renorm,
+                                           int32_t* __restrict__ idx, float* __restrict__ wout)
+{
+    int sel[8];
+    float selv[8];
+    for (int j = 0; j < k; ++j) {
+        int best = 0x7fffffff;
+        float bv = -INFINITY;
+        for (int e = part; e < E; e += 4) {
+            bool taken = false;
+            for (int q = 0; q < j; ++q) taken |= (sel[q] == e);
+            if (taken) continue;
+            float v = lg[e];
+            v = (v != v) ? -INFINITY : v;
+            if (best == 0x7fffffff || v > bv) { best = e; bv = v; }
+        }
+#pragma unroll
+        for (int off = 1; off <= 2; off <<= 1) {
+            const float ov = __shfl_xor(bv, off, 64);
+            const int oi = __shfl_xor(best, off, 64);
+            if (oi != 0x7fffffff && (best == 0x7fffffff || ov > bv || (ov == bv && oi < best))) { bv = ov; best = oi; }
+        }
+        sel[j] = best;
+        selv[j] = bv;
+    }
+    const float m = selv[0];
+    float sum = 0.0f;
+    for (int e = part; e < E; e += 4) {
+        float v = lg[e];
+        v = (v != v) ? -INFINITY : v;
+        sum += expf(v - m);
+    }
+    sum += __shfl_xor(sum, 1, 64);
+    sum += __shfl_xor(sum, 2, 64);
+    float ps[8], psum = 0.0f;
+    for (int j = 0; j < k; ++j) { ps[j] = expf(selv[j] - m) / sum; psum += ps[j]; }
+    if (store && part == 0)
+        for (int j = 0; j < k; ++j) {
+            idx[(size_t)t * k + j] = sel[j];
+            wout[(size_t)t * k + j] = renorm ? ps[j] / psum : ps[j];
+        }
+}
+
 // One block = 64 tokens, wave w = tokens 16w..16w+15 over the whole contraction; NT tiles of 16 experts per
 // pass.  MFMA roles: rows = experts (A operand: the gate matrix, staged through LDS in chunks of 64 columns
 // shared by the four waves), columns = tokens (B operand: the lane's own 16-byte pieces of X, NXP chunks
@@ -248,7 +295,7 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_mfma_kernel(
             const int tk = i / E, e = i - tk * E;
             if (tok0w + tk < T) logits[(size_t)tok0w * E + i] = logit_lds[(wave * 16 + tk) * e_pitch + e];
         }
-        if (lane < 16 && tok < T) route_one(logit_lds + (wave * 16 + lane) * e_pitch, tok, E, k, renorm, idx, wout);
+        route_four(logit_lds + (wave * 16 + (lane >> 2)) * e_pitch, lane & 3, tok0w + (lane >> 2), tok0w + (lane >> 2) < T, E, k, renorm, idx, wout);
     }
 }
 
@@ -397,7 +444,7 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_mfma_dma_kernel(
             const int tk = i / E, e = i - tk * E;
             if (tok0w + tk < T) logits[(size_t)tok0w * E + i] = logit_lds[(wave * 16 + tk) * e_pitch + e];
         }
-        if (lane < 16 && tok < T) route_one(logit_lds + (wave * 16 + lane) * e_pitch, tok, E, k, renorm, idx, wout);
+        route_four(logit_lds + (wave * 16 + (lane >> 2)) * e_pitch, lane & 3, tok0w + (lane >> 2), tok0w + (lane >> 2) < T, E, k, renorm, idx, wout);
     }
 }
 
