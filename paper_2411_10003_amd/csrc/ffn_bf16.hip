@@ -23,6 +23,7 @@
 // columns of one row.  The two rows of waves of a block alternate between fetching fragments and
 // multiplying, half an iteration apart.
 #include "internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -96,6 +97,11 @@ __device__ __forceinline__ void lds_frag_kcontig(bf16x8& f, uint32_t addr)
 {
     asm volatile("ds_read_b128 %0, %1" : "=v"(f) : "v"(addr));
 }
+template <int IMM>
+__device__ __forceinline__ void lds_frag_kcontig_at(bf16x8& f, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f) : "v"(addr), "n"(IMM));
+}
 // The transposing load works on blocks of 16 lanes: lane s of a block points at 4 consecutive columns
 // of step s/4; lane i of the block receives column i of steps 0..3.  Two loads give the 8 steps of a
 // lane in the same order as the K-contiguous fragment.
@@ -105,6 +111,15 @@ __device__ __forceinline__ void lds_frag_kmajor(bf16x8& f, uint32_t addr)
     s16x4 lo, hi;
     asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3"
                  : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(ROW4_BYTES));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    f = __builtin_bit_cast(bf16x8, v);
+}
+template <int ROW4_BYTES, int IMM>
+__device__ __forceinline__ void lds_frag_kmajor_at(bf16x8& f, uint32_t addr)
+{
+    s16x4 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:%3\n\tds_read_b64_tr_b16 %1, %2 offset:%4"
+                 : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(IMM), "n"(IMM + ROW4_BYTES));
     const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     f = __builtin_bit_cast(bf16x8, v);
 }
@@ -382,17 +397,32 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 fb_addr[j] = OPER_BYTES + kmajor_off<BN>(krow, wn * WN + j * 32 + cofs);
         }
     }
-    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, int half) {
+    // The stage base is the only part of a fragment address that changes from slice to slice, and every vector
+    // instruction of the fetching wave takes an issue slot from the matrix instructions of its partner: fragments
+    // that lie a constant distance apart (K-contiguous: 32 rows = 2 KB; the second 16 steps of a K-major operand)
+    // share one address register and differ in the instruction's immediate offset.
+    static_assert(TM == 4 && TN == 2, "the fragment reads below are written out for 4 x 2 fragments");
+    uint32_t fa_h1 = fa_addr[0] ^ 32u, fb_h1 = fb_addr[0] ^ 32u;       // K-contiguous: step half 1 of fragment 0
+    auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, auto HALF) {
+        constexpr int half = decltype(HALF)::value;
         const uint32_t st = lds0 + (uint32_t)stage * STAGE_BYTES;
+        if constexpr (A_KMAJOR) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            if (A_KMAJOR) lds_frag_kmajor<4 * BM * 2>(fa[i], st + fa_addr[i] + half * A_HALF);
-            else lds_frag_kcontig(fa[i], st + (fa_addr[i] ^ (half ? 32u : 0u)));
+            for (int i = 0; i < TM; ++i) lds_frag_kmajor_at<4 * BM * 2, half * (int)A_HALF>(fa[i], st + fa_addr[i]);
+        } else {
+            const uint32_t a = st + (half ? fa_h1 : fa_addr[0]);
+            lds_frag_kcontig_at<0>(fa[0], a);
+            lds_frag_kcontig_at<2048>(fa[1], a);
+            lds_frag_kcontig_at<4096>(fa[2], a);
+            lds_frag_kcontig_at<6144>(fa[3], a);
         }
+        if constexpr (B_KMAJOR) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            if (B_KMAJOR) lds_frag_kmajor<4 * BCOLS * 2>(fb[j], st + fb_addr[j] + half * B_HALF);
-            else lds_frag_kcontig(fb[j], st + (fb_addr[j] ^ (half ? 32u : 0u)));
+            for (int j = 0; j < TN; ++j) lds_frag_kmajor_at<4 * BCOLS * 2, half * (int)B_HALF>(fb[j], st + fb_addr[j]);
+        } else {
+            const uint32_t bb = st + (half ? fb_h1 : fb_addr[0]);
+            lds_frag_kcontig_at<0>(fb[0], bb);
+            lds_frag_kcontig_at<2048>(fb[1], bb);
         }
     };
     auto wait_frags = [&]() {
@@ -447,8 +477,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         for (int t = 0; t < k_cnt; ++t) {
             // fetch phase.  Ring slot (t+4) % 5 held slice t-1, which every wave finished reading at
             // least one barrier ago.
-            load_frags(fa0, fb0, cur, 0);
-            load_frags(fa1, fb1, cur, 1);
+            load_frags(fa0, fb0, cur, std::integral_constant<int, 0>{});
+            load_frags(fa1, fb1, cur, std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
             if (t + L < k_cnt) issue_next();
             // this wave's pieces of slice t+1 must have landed before the barrier lets anyone read them
