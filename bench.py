@@ -27,7 +27,7 @@ PEAK_F32_TFLOPS = 157.3        # fp32 vector
 PEAK_HBM_GBS = 8000.0          # HBM3E
 # HBM-side bytes of all grouped_gemm_kernel launches of one step, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
 # plain copy of known size (profiles/grouped_gemm_cfg3_pmc_traffic.txt); counters cannot be read from inside this run.
-MEASURED_FFN_TRAFFIC_BYTES = {3: 1.051e11}
+MEASURED_FFN_TRAFFIC_BYTES = {3: 1.105e11}
 
 
 def log(*a):
