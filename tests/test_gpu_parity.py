@@ -46,6 +46,9 @@ GATE_CASES = [
     _cfg(1, T=300, d=128, h=64, E=100, k=3, P=10, n_replicas=1),
     _cfg(1, T=300, d=1024, h=64, E=128, k=2, P=8, n_replicas=1),   # two passes of 64 experts, whole chunks
     _cfg(1, T=65, d=64, h=64, E=5, k=2, P=5, n_replicas=1),
+    _cfg(1, T=130, d=256, h=64, E=48, k=2, P=8, n_replicas=1),     # bf16, E a multiple of 16 the ring kernel does not take
+    _cfg(1, T=130, d=192, h=64, E=80, k=2, P=8, n_replicas=1),     # two passes, the second one partly empty
+    _cfg(0, T=130, d=128, E=16, k=2, P=4),                         # fp32 tokens, two whole chunks
 ]
 
 
