@@ -49,6 +49,7 @@ GATE_CASES = [
     _cfg(1, T=130, d=256, h=64, E=48, k=2, P=8, n_replicas=1),     # bf16, E a multiple of 16 the ring kernel does not take
     _cfg(1, T=130, d=192, h=64, E=80, k=2, P=8, n_replicas=1),     # two passes, the second one partly empty
     _cfg(0, T=130, d=128, E=16, k=2, P=4),                         # fp32 tokens, two whole chunks
+    _cfg(1, T=100, d=8192, h=64),                                  # rows longer than any workload's
 ]
 
 
