@@ -93,10 +93,6 @@ __device__ __forceinline__ uint32_t kmajor_off(int krow, int col) { return krow 
 // Fragment reads are issued as assembly and waited for by hand (WAIT_FRAGS below): the compiler's
 // own wait insertion cannot express "the set loaded one iteration ago is complete" and would stall
 // every MFMA group on the fragments that were only just requested for the next iteration.
-__device__ __forceinline__ void lds_frag_kcontig(bf16x8& f, uint32_t addr)
-{
-    asm volatile("ds_read_b128 %0, %1" : "=v"(f) : "v"(addr));
-}
 template <int IMM>
 __device__ __forceinline__ void lds_frag_kcontig_at(bf16x8& f, uint32_t addr)
 {
@@ -104,16 +100,7 @@ __device__ __forceinline__ void lds_frag_kcontig_at(bf16x8& f, uint32_t addr)
 }
 // The transposing load works on blocks of 16 lanes: lane s of a block points at 4 consecutive columns
 // of step s/4; lane i of the block receives column i of steps 0..3.  Two loads give the 8 steps of a
-// lane in the same order as the K-contiguous fragment.
-template <int ROW4_BYTES>
-__device__ __forceinline__ void lds_frag_kmajor(bf16x8& f, uint32_t addr)
-{
-    s16x4 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %2 offset:%3"
-                 : "=&v"(lo), "=&v"(hi) : "v"(addr), "n"(ROW4_BYTES));
-    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    f = __builtin_bit_cast(bf16x8, v);
-}
+// lane in the same order as the K-contiguous fragment.  IMM: a constant distance added to the address.
 template <int ROW4_BYTES, int IMM>
 __device__ __forceinline__ void lds_frag_kmajor_at(bf16x8& f, uint32_t addr)
 {
