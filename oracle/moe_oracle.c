@@ -362,6 +362,19 @@ void orc_ffn_bwd_hidden(const float* X, const int32_t* idx, const int32_t* group
     }
 }
 
+/* The same for a list of hidden units of one group, one unit per thread: every unit is the call above,
+ * unchanged (outer loop only).  Row i of each output belongs to hidden unit js[i]. */
+void orc_ffn_bwd_hidden_many(const float* X, const int32_t* idx, const int32_t* group_of_expert,
+                             const float* W1, const float* W2, const float* W3, int d, int h, int k, int A, int act,
+                             const float* dYa, int g, const int32_t* js, int n_js,
+                             double* dW2rows, double* dW1cols, double* dW3cols)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < n_js; ++i)
+        orc_ffn_bwd_hidden(X, idx, group_of_expert, W1, W2, W3, d, h, k, A, act, dYa, g, js[i],
+                           dW2rows + (size_t)i * d, dW1cols + (size_t)i * d, dW3cols ? dW3cols + (size_t)i * d : NULL);
+}
+
 /* Gradient of the send (fourth all-to-all): dX[t,:] = sum_j dXp[pos[t*k+j],:]. */
 void orc_dispatch_bwd(const double* dXp, const int32_t* pos, int T, int d, int k, double* dX)
 {

@@ -186,6 +186,23 @@ def ffn_bwd_hidden(X, idx, group_of_expert, W1, W2, W3, k: int, act: str, dYa, g
     return r2, c1, c3
 
 
+def ffn_bwd_hidden_many(X, idx, group_of_expert, W1, W2, W3, k: int, act: str, dYa, g: int, js):
+    """ffn_bwd_hidden for several hidden units of one group (one per thread): rows of (dW2[g][js,:],
+    dW1[g][:,js].T, dW3[g][:,js].T or None)."""
+    X, idx, goe = _f32(X), _i32(idx).reshape(-1), _i32(group_of_expert)
+    W1, W2 = _f32(W1), _f32(W2)
+    W3 = _f32(W3) if act == "swiglu" else None
+    dYa, js = _f32(dYa), _i32(js).reshape(-1)
+    d, h, A = X.shape[1], W1.shape[2], idx.size
+    assert dYa.shape == (A, d) and 0 <= g < W1.shape[0] and (js.size == 0 or (js.min() >= 0 and js.max() < h))
+    r2 = np.empty((js.size, d), dtype=np.float64)
+    c1 = np.empty((js.size, d), dtype=np.float64)
+    c3 = np.empty((js.size, d), dtype=np.float64) if W3 is not None else None
+    lib().orc_ffn_bwd_hidden_many(_p(X), _p(idx), _p(goe), _p(W1), _p(W2), _p(W3), d, h, k, A, ACT[act],
+                                  _p(dYa), int(g), _p(js), int(js.size), _p(r2), _p(c1), _p(c3))
+    return r2, c1, c3
+
+
 def ffn_bwd_weights(X, idx, group_of_expert, W1, W2, W3, k: int, act: str, dYa, G: int):
     """Full weight gradients (small cases): loops ffn_bwd_hidden over every group and hidden unit."""
     d, h = X.shape[1], W1.shape[2]

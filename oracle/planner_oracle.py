@@ -1,7 +1,7 @@
 """CPU oracle of the planner -- TEST INFRASTRUCTURE, NOT PRODUCT.
 
-Plain Python/NumPy statement of the paper's performance model (Section 4.2, Eqs. 1-7; Section 5.3,
-Eq. 8) and of its greedy search (Section 4.3, Algorithm 1, balance test of Eq. 9).  Only tests, the
+Plain Python/NumPy statement of the paper's performance model (Section 4.2, Eqs. 1-6; Section 5.3,
+Eq. 8) and of its greedy search (Section 4.3, Algorithm 1, balance test of Eq. 7).  Only tests, the
 smoke check and the benchmark's CPU-baseline leg import this module; it imports nothing from the GPU
 package.  Slow on purpose: after every selection the per-device loads are recomputed from the
 definition of a lightweight placement (Section 4.1), never updated in place.
@@ -42,8 +42,8 @@ class PlannerModel:
     t: float                   # computation throughput, inputs/s
     T_FNEC: float = 0.0        # forward time of the non-MoE layer (Eq. 8 only)
     T_BNEC: float = 0.0        # backward time of the non-MoE layer (Eq. 8 only)
-    overlap: bool = False      # False: Eq. 7, True: Eq. 8
-    alpha: float = 1.0         # coefficient of the balance test (Eq. 9)
+    overlap: bool = False      # False: Eq. 6, True: Eq. 8
+    alpha: float = 1.0         # coefficient of the balance test (Eq. 7)
 
 
 def owner_of(e: int, E: int, D: int) -> int:
@@ -90,7 +90,7 @@ def t_agg(s: int, n: int, D: int, m: PlannerModel) -> float:
 
 
 def layer_time(R: Sequence[int], H: Sequence[int], s: int, n: int, m: PlannerModel) -> float:
-    """T'(R, H, s, n): Eq. 7, or Eq. 8 when the scheduler hides Trans and Agg behind computation."""
+    """T'(R, H, s, n): Eq. 6, or Eq. 8 when the scheduler hides Trans and Agg behind computation."""
     D = len(H)
     a2a = t_a2a(R, m)
     fec = t_fec(H, m)
@@ -106,7 +106,7 @@ def layer_time(R: Sequence[int], H: Sequence[int], s: int, n: int, m: PlannerMod
 
 
 def balanced(H: Sequence[int], total_inputs: int, E: int, m: PlannerModel) -> bool:
-    """Eq. 9: max(H) - min(H) < alpha * I / E."""
+    """Eq. 7: max(H) - min(H) < alpha * I / E."""
     return float(int(max(H)) - int(min(H))) < (m.alpha * float(total_inputs)) / float(E)
 
 
@@ -131,46 +131,62 @@ def placement(D: int, E: int, L: Sequence[int], n_bottoms: Sequence[Sequence[int
     return hosts
 
 
+def next_selection(gating: np.ndarray, H: np.ndarray, chosen: Sequence[int], n: int):
+    """One step of the search (Section 4.3): the device with the largest load (ties: lowest index) gives up its
+    heaviest expert that has not been selected yet (ties: lowest id), and the n devices that hold the fewest of
+    that expert's inputs do not receive it.  None when that device has no expert left to give."""
+    D, E = gating.shape
+    heaviest = int(np.argmax(H))
+    totals = gating.sum(axis=0)
+    left = [e for e in range(E) if owner_of(e, E, D) == heaviest and e not in chosen]
+    if not left:
+        return None
+    e_sel = min(left, key=lambda e: (-int(totals[e]), e))
+    return heaviest, e_sel, bottom_k(gating, e_sel, n)
+
+
 def greedy_search(gating: np.ndarray, n: int, m: PlannerModel) -> Dict[str, object]:
-    """Algorithm 1.  Returns the search trace and the placement of its first `cnt` selections."""
+    """The greedy search of Section 4.3 (Algorithm 1), stated as: grow a chain of placements, each adding one
+    selection to the one before, until the load is balanced or the heaviest device has nothing left; evaluate
+    every placement of the chain with the performance model from its own definition; return the first placement
+    of the chain whose time is the smallest (a later one has to be strictly faster to be preferred)."""
     gating = np.asarray(gating, dtype=np.int64)
     D, E = gating.shape
     assert E % D == 0 and 0 <= n <= D - 1
     total = int(gating.sum())
-    per_expert = gating.sum(axis=0)
 
-    L: List[int] = []
-    n_bottoms: List[List[int]] = []
-    H, R = loads(gating, placement(D, E, L, n_bottoms))
-    T_base = layer_time(R, H, 0, 0, m)
-    T_output = T_base
-    cnt = 0
-    trace = []
-    while not balanced(H, total, E, m):
-        i = int(np.argmax(H))                              # first maximum
-        mine = [e for e in range(E) if owner_of(e, E, D) == i and e not in L]
-        if not mine:
+    chain = [([], [])]                                     # (selected experts, devices each of them skips)
+    donors = []
+    while True:
+        experts, skipped = chain[-1]
+        H, _ = loads(gating, placement(D, E, experts, skipped))
+        if balanced(H, total, E, m):
             break
-        e_sel = min(mine, key=lambda e: (-int(per_expert[e]), e))
-        nb = bottom_k(gating, e_sel, n)
-        L.append(e_sel)
-        n_bottoms.append(nb)
-        s = len(L)
-        H, R = loads(gating, placement(D, E, L, n_bottoms))
-        T_changed = layer_time(R, H, s, n, m)
-        if T_changed < T_output:
-            T_output = T_changed
-            cnt = s
-        trace.append(dict(device=i, expert=e_sel, n_bottom=nb, H=H.copy(), R=R.copy(), T=T_changed))
+        step = next_selection(gating, H, experts, n)
+        if step is None:
+            break
+        device, e_sel, nb = step
+        donors.append(device)
+        chain.append((experts + [e_sel], skipped + [nb]))
+
+    evaluated = []
+    for experts, skipped in chain:
+        H, R = loads(gating, placement(D, E, experts, skipped))
+        s = len(experts)
+        evaluated.append((layer_time(R, H, s, n if s else 0, m), H, R))
+    times = [t for t, _, _ in evaluated]
+    cnt = min(range(len(chain)), key=lambda i: (times[i], i))          # first of the smallest times
+    L, n_bottoms = chain[-1]
+    trace = [dict(device=donors[i - 1], expert=L[i - 1], n_bottom=n_bottoms[i - 1], H=evaluated[i][1].copy(),
+                  R=evaluated[i][2].copy(), T=times[i]) for i in range(1, len(chain))]
 
     hosts = placement(D, E, L[:cnt], n_bottoms[:cnt])
-    H_out, R_out = loads(gating, hosts)
     expert_dest = np.empty((D, E), dtype=np.int32)
     for j in range(D):
         for e in range(E):
             expert_dest[j, e] = j if hosts[j, e] else owner_of(e, E, D)
     return dict(L=L, n_bottoms=n_bottoms, cnt=cnt, hosts=hosts, expert_dest=expert_dest,
-                H=H_out, R=R_out, T_base=T_base, T_output=T_output, trace=trace)
+                H=evaluated[cnt][1], R=evaluated[cnt][2], T_base=times[0], T_output=times[cnt], trace=trace)
 
 
 def top_policy(gating: np.ndarray, r: int) -> np.ndarray:

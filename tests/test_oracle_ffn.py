@@ -185,6 +185,12 @@ def test_backward_vs_finite_differences(orc, ci):
     dYa = dYp[pos].astype(np.float32)                  # by assignment; exact enough: compared at 1e-5
     Gn = int(goe.max()) + 1
     dW1, dW2, dW3 = orc.ffn_bwd_weights(X, idx, goe, W1, W2, W3, k, act, dYa, Gn)
+    # the threaded form over a list of hidden units is the same call per unit: same bits, any order of units
+    js = np.arange(cfg.h, dtype=np.int32)[::-1].copy()
+    for g in range(Gn):
+        r2, c1, c3 = orc.ffn_bwd_hidden_many(X, idx, goe, W1, W2, W3, k, act, dYa, g, js)
+        assert np.array_equal(r2, dW2[g][js]) and np.array_equal(c1, dW1[g][:, js].T)
+        assert c3 is None if W3 is None else np.array_equal(c3, dW3[g][:, js].T)
 
     def fd(arr, index, fn):
         old = arr[index]

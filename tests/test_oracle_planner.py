@@ -1,4 +1,4 @@
-"""Pins of the planner oracle (performance model Eqs. 1-8, balance test Eq. 9, Algorithm 1).
+"""Pins of the planner oracle (performance model Eqs. 1-6 and 8, balance test Eq. 7, Algorithm 1).
 
 The expected numbers of the worked examples were derived by hand from the paper's rules (the trace is
 written out in the docstrings), never produced by the code under test.  The property tests restate the
@@ -24,14 +24,14 @@ def model(**kw):
 
 
 def test_equations_on_hand_numbers():
-    """Eqs. 1-7 on numbers small enough to check in the head (D = 4)."""
+    """Eqs. 1-6 on numbers small enough to check in the head (D = 4)."""
     m = model(size_input=2.0, B=4.0, t=8.0, size_params=16.0, size_grads=8.0)
     R, H = [10, 2, 1, 2], [16, 4, 4, 8]
     assert po.t_a2a(R, m) == 10 * 2.0 / 4.0                          # Eq. 1: the slowest receiver
     assert po.t_fec(H, m) == 16 / 8.0                                # Eq. 2: the most loaded device
     assert po.t_trans(3, 1, 4, m) == 3 * (4 - 1) * 16.0 / (4 * 4.0)  # Eq. 4
     assert po.t_agg(3, 1, 4, m) == 3 * (4 - 1) * 8.0 / (4 * 4.0)     # Eq. 5
-    # Eq. 7: four all-to-alls, forward + backward (= 2 x forward) expert computation, Trans, Agg
+    # Eq. 6: four all-to-alls, forward + backward (= 2 x forward) expert computation, Trans, Agg
     assert po.layer_time(R, H, 3, 1, m) == 4 * 5.0 + 3 * 2.0 + 9.0 + 4.5
     assert po.layer_time(R, H, 0, 0, m) == 26.0
 
