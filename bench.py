@@ -25,9 +25,27 @@ METRIC = "MoE-layer tokens/sec/GPU (gate+dispatch+grouped FFN+combine); FFN MFMA
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3        # fp32 vector
 PEAK_HBM_GBS = 8000.0          # HBM3E
-# HBM-side bytes of all grouped_gemm_kernel launches of one step, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
-# plain copy of known size (profiles/grouped_gemm_cfg3_pmc_traffic.txt); counters cannot be read from inside this run.
-MEASURED_FFN_TRAFFIC_BYTES = {3: 1.105e11}
+# HBM-side bytes of all grouped_gemm_kernel launches of one step come from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by
+# a plain copy of known size; counters cannot be read from inside this run, so the figure is parsed from the committed
+# summary of those two runs, which states the workload (flops per step) it was measured on.
+TRAFFIC_PROFILES = {3: os.path.join(ROOT, "profiles", "grouped_gemm_cfg3_pmc_traffic.txt")}
+
+
+def measured_traffic(cfg_index: int, flops_per_step: float):
+    """Bytes per step from the counter summary of this configuration, or None if there is none.  The summary names
+    the flops per step of the run it was taken from: a summary of another workload is an error, not a number."""
+    import re
+    path = TRAFFIC_PROFILES.get(cfg_index)
+    if path is None or not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m = re.search(r"traffic per step = ([0-9.eE+]+) bytes.*algorithmic flops per step ([0-9.eE+]+)", text)
+    if not m:
+        raise SystemExit(f"bench.py: {path} has no 'traffic per step' line")
+    traffic, flops = float(m.group(1)), float(m.group(2))
+    if abs(flops - flops_per_step) > 2e-3 * flops_per_step:
+        raise SystemExit(f"bench.py: {path} was measured on {flops:.4e} flops per step, this run does {flops_per_step:.4e}")
+    return traffic
 
 
 def log(*a):
@@ -81,29 +99,32 @@ class PowerSampler:
                 "cap_w": self.cap_w, "samples": len(self.samples)}
 
 
-def cpu_baseline(cfg, inp, expert_dest, n_tokens: int, n_hidden: int):
-    """The oracle as it stands on the first n_tokens tokens of the workload: the whole layer pass,
-    weight gradients on n_hidden hidden units per group with their time scaled to all h."""
+def cpu_baseline(cfg, inp, n_tokens: int, n_hidden: int):
+    """The oracle as it stands, timed on a bounded sample of the same workload, in two legs.
+    Rows: the whole layer pass (every call of a step except the weight gradients) on the first n_tokens tokens;
+    its time scales with the tokens.  Weight gradients: the contraction over ALL hosted rows of the workload for
+    n_hidden hidden units of every hosted group; its time scales with the hidden units.  The plan comes from the
+    oracle's own routing of the full batch."""
     from oracle import moe_oracle as orc
     from paper_2411_10003_amd import workload as wl
     orc.build()
-    k, act = cfg.k, cfg.act
+    k, act, T = cfg.k, cfg.act, cfg.T
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    r_full = orc.route(inp["X"], inp["Wg"], inp["bg"], k, cfg.renorm)       # untimed: where the plan comes from
+    expert_dest = wl.make_plan(cfg, r_full["counts"], threshold=(cfg.index == 4))
+    goe = wl.group_of_expert(expert_dest, cfg.self_dest)
     X = inp["X"][:n_tokens]
     t0 = time.perf_counter()
     r = orc.route(X, inp["Wg"], inp["bg"], k, cfg.renorm)
     lay = orc.place(r["idx"], r["counts"], expert_dest, cfg.P)
-    goe = wl.group_of_expert(expert_dest, cfg.self_dest)
     idx = r["idx"].reshape(-1)
     hosted = orc.hosted_assignments(idx, goe)
-    Xp = orc.dispatch(X, lay["perm"], k)
+    orc.dispatch(X, lay["perm"], k)
     Y = orc.ffn_fwd(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, hosted)
     Yp = inp["Yp_fill"][: n_tokens * k].astype(np.float64)
     Yp[lay["pos"][hosted]] = Y
-    out = orc.combine(Yp, lay["pos"], r["w"], k)
-    t_rows = time.perf_counter() - t0
-    t_w = 0.0
+    orc.combine(Yp, lay["pos"], r["w"], k)
     if cfg.backward:
-        t0 = time.perf_counter()
         dOut = inp["dOut"][:n_tokens]
         dYp, dw = orc.combine_bwd(dOut, Yp, lay["pos"], r["w"], k)
         dXh = orc.ffn_bwd_rows(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, hosted, dYp[lay["pos"][hosted]])
@@ -111,23 +132,55 @@ def cpu_baseline(cfg, inp, expert_dest, n_tokens: int, n_hidden: int):
         dXp[lay["pos"][hosted]] = dXh
         orc.dispatch_bwd(dXp, lay["pos"], k)
         orc.gate_bwd(dw, r["logits"], r["idx"], cfg.renorm)
-        t_rows += time.perf_counter() - t0
-        t0 = time.perf_counter()
-        dYa = dYp[lay["pos"]].astype(np.float32)
-        G = int((np.asarray(expert_dest) == cfg.self_dest).sum())
-        for g in range(G):
-            for j in range(n_hidden):
-                orc.ffn_bwd_hidden(X, idx, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, dYa, g, j)
-        t_w = (time.perf_counter() - t0) * (cfg.h / n_hidden)
-    total = t_rows + t_w
-    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t_rows = time.perf_counter() - t0
+    rows_scaled = t_rows * (T / n_tokens)
+    if not cfg.backward:
+        return {"value": T / rows_scaled, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                "sample": f"whole forward pass on the first {n_tokens} of {T} tokens in {t_rows:.1f} s ({threads} threads), "
+                          f"scaled to {rows_scaled:.1f} s for the batch"}
+    # weight gradients over every hosted row of the batch (dYp = w * dOut does not depend on the expert outputs)
+    idx_full = r_full["idx"].reshape(-1)
+    dYa = (r_full["w"].reshape(-1, 1) * np.repeat(inp["dOut"], k, axis=0)).astype(np.float32)
+    G = int((np.asarray(expert_dest) == cfg.self_dest).sum())
+    M = int((goe[idx_full] >= 0).sum())
+    rng = np.random.default_rng(0)
+    js = np.sort(rng.choice(cfg.h, size=n_hidden, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    for g in range(G):
+        orc.ffn_bwd_hidden_many(inp["X"], idx_full, goe, inp["W1"], inp["W2"], inp.get("W3"), k, act, dYa, g, js)
+    t_w = time.perf_counter() - t0
+    w_scaled = t_w * (cfg.h / n_hidden)
+    total = rows_scaled + w_scaled
     return {
-        "value": n_tokens / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-        "sample": (f"first {n_tokens} of {cfg.T} tokens, whole layer pass in {total:.1f} s "
-                   f"(rows {t_rows:.1f} s; weight gradients on {n_hidden} of {cfg.h} hidden units per group, "
-                   f"scaled to {t_w:.1f} s)") if cfg.backward else
-                  f"first {n_tokens} of {cfg.T} tokens, whole forward pass in {total:.1f} s",
+        "value": T / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": (f"scaled: rows (every call but the weight gradients) on the first {n_tokens} of {T} tokens in {t_rows:.1f} s "
+                   f"({threads} threads over rows) x {T / n_tokens:.0f} = {rows_scaled:.0f} s; weight gradients over all {M} hosted "
+                   f"rows on {n_hidden} of {cfg.h} hidden units per group in {t_w:.1f} s ({min(threads, n_hidden)} threads over "
+                   f"hidden units) x {cfg.h / n_hidden:.0f} = {w_scaled:.0f} s"),
     }
+
+
+def ffn_group_bounds(cfg, group_rows, backward: bool):
+    """Per hosted group, the time the expert computation needs at the published peaks: bound_g =
+    max(flops_g / MFMA peak, bytes_g / HBM peak).  A group of few rows is bound by reading its weights (and, in
+    the backward pass, writing its fp32 weight gradients), a large one by the matrix cores.  Bytes: every operand
+    and result of the group's contractions once (weights, saved pre-activations, activations, gradients)."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    d, h, nm = cfg.d, cfg.h, cfg.n_mats
+    peak = (PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS) * 1e12
+    out = []
+    for m in group_rows:
+        flops = 2.0 * m * d * h * nm * (3 if backward else 1)
+        w_bytes = nm * d * h * es
+        # forward: Xp in, Z (and U) and the activation out, the activation in again, Yp out
+        nbytes = w_bytes + m * (d * es + nm * h * es + h * es + d * es)
+        if backward:
+            # dYp in twice, Z (and U) in, dZ (and dU) out and in twice, the activation and Xp in, dXp out, the weights
+            # again, the fp32 weight gradients out (written as zeros even for an empty group)
+            nbytes += w_bytes + nm * d * h * 4 + m * (2 * d * es + (nm - 1) * h * es + 3 * (nm - 1) * h * es + h * es + d * es + d * es)
+        t_f, t_b = flops / peak, nbytes / (PEAK_HBM_GBS * 1e9)
+        out.append({"rows": int(m), "bound_us": round(max(t_f, t_b) * 1e6, 1), "bound": "mfma" if t_f >= t_b else "hbm"})
+    return out
 
 
 def main():
@@ -144,6 +197,11 @@ def main():
                          "for profiler runs, so that per-kernel averages cover the step's launches only")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) to scale rocprofv3 FETCH_SIZE/WRITE_SIZE readings")
+    ap.add_argument("--no-calib", action="store_true",
+                    help="skip the two calibration kernels (streaming copy, register-only bf16 MFMA loop) that give the measured peaks")
+    ap.add_argument("--recompute-act", action="store_true",
+                    help="backward recomputes the activation from the saved pre-activations instead of reading the forward "
+                         "pass's copy in the workspace (for callers that share one workspace between layers)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is one GPU's share of the layer; it has no multi-GPU path (use --gpus 1)")
@@ -174,6 +232,10 @@ def main():
 
     hd = binding.Handle(T=cfg.T, d=cfg.d, h=cfg.h, E=cfg.E, k=cfg.k, P=cfg.P, self_dest=cfg.self_dest,
                         G=cfg.G_max, dtype=dt, act=cfg.act, renorm=cfg.renorm, device=dev)
+    # this layer keeps its workspace from its forward to its backward pass, so the activation the forward pass
+    # left there is read by the backward pass instead of being recomputed (moe_set_act_saved)
+    act_saved = cfg.backward and dt == "bf16" and not args.recompute_act
+    hd.set_act_saved(act_saved)
     b = binding.LayerBuffers(hd, cfg.backward)
     b.Yp.copy_(up(inp["Yp_fill"], dt))
     if cfg.backward:
@@ -197,7 +259,8 @@ def main():
         mark(0)
         hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w); mark(1)
         hd.expert_counts(b.idx, b.counts); mark(2)
-        hd.dispatch(expert_dest, X, b.idx, b.counts, b.layout, b.Xp); mark(3)
+        # counts -> dispatch on the same idx and workspace with nothing in between: the histograms are not rebuilt
+        hd.dispatch_after_counts(expert_dest, X, b.idx, b.counts, b.layout, b.Xp); mark(3)
         hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z, b.U); mark(4)
         hd.combine(b.Yp, b.layout.pos, b.w, b.out); mark(5)
         if cfg.backward:
@@ -238,8 +301,11 @@ def main():
         elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
-    call_ms = {c: float(np.mean([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)]))
-               for i, c in enumerate(calls)}
+    call_all = {c: np.array([events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)])
+                for i, c in enumerate(calls)}
+    call_ms = {c: float(np.mean(v)) for c, v in call_all.items()}
+    step_all = np.array([events[s][0].elapsed_time(events[s][n_ev - 1]) for s in range(args.steps)])
+    ffn_all = call_all["expert_ffn_fwd"] + call_all.get("expert_ffn_bwd", 0.0)
 
     # algorithmic work
     es = 2 if dt == "bf16" else 4
@@ -258,15 +324,62 @@ def main():
     }
     per_call = {}
     for c in calls:
-        e = {"ms": round(call_ms[c], 4)}
+        e = {"ms": round(call_ms[c], 4), "median_ms": round(float(np.median(call_all[c])), 4),
+             "min_ms": round(float(call_all[c].min()), 4)}
         if c in hbm_bytes:
             gbs = hbm_bytes[c] / (call_ms[c] * 1e-3) / 1e9
             e.update({"GB/s": round(gbs, 1), "hbm_frac": round(gbs / PEAK_HBM_GBS, 4)})
+        if c == "gate_topk":
+            # co-bound: the tokens stream from HBM while 2 E flops per element run on the fp32 matrix instruction
+            # (157.3 TFLOP/s); at E = 64 the arithmetic takes longer than the stream at their peaks
+            gflop = 2.0 * T * d * E
+            t_hbm, t_mat = hbm_bytes[c] / (PEAK_HBM_GBS * 1e9), gflop / (PEAK_F32_TFLOPS * 1e12)
+            e.update({"TFLOP/s": round(gflop / (call_ms[c] * 1e-3) / 1e12, 2),
+                      "matrix_frac": round(gflop / (call_ms[c] * 1e-3) / 1e12 / PEAK_F32_TFLOPS, 4),
+                      "bound": "fp32 matrix rate" if t_mat > t_hbm else "hbm",
+                      "us_at_peak": {"hbm": round(t_hbm * 1e6, 1), "fp32_matrix": round(t_mat * 1e6, 1)}})
         if c == "expert_ffn_fwd":
             e.update({"TFLOP/s": round(fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
         if c == "expert_ffn_bwd":
             e.update({"TFLOP/s": round(2 * fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
         per_call[c] = e
+
+    # ---- measured peaks of this GPU today: a plain streaming copy and a register-only bf16 MFMA loop
+    measured_peak = None
+    if not args.no_calib:
+        nb = 1 << 30
+        src = torch.empty(nb, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.empty(cus * 512, dtype=torch.float32, device=dev)
+        iters = 40000
+        binding.calib_copy(src, dst)
+        mfma_flops = binding.calib_mfma(sink, iters)
+        torch.cuda.synchronize()
+        reps = 5
+        ce = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps + 1)]
+        ce[0].record()
+        for i in range(reps):
+            binding.calib_copy(src, dst); ce[i + 1].record()
+        with PowerSampler() as cal_power:
+            for i in range(reps):
+                binding.calib_mfma(sink, iters); ce[reps + i + 1].record()
+            torch.cuda.synchronize()
+        t_copy = np.array([ce[i].elapsed_time(ce[i + 1]) for i in range(reps)])
+        t_mfma = np.array([ce[reps + i].elapsed_time(ce[reps + i + 1]) for i in range(reps)])
+        measured_peak = {
+            "copy_GB/s": round(2.0 * nb / (float(np.median(t_copy)) * 1e-3) / 1e9, 1),
+            "copy_what": "1 GiB read + 1 GiB written by a plain 16-byte-per-lane kernel, median of 5",
+            "mfma_TFLOP/s": round(mfma_flops / (float(np.median(t_mfma)) * 1e-3) / 1e12, 1),
+            "mfma_what": f"{cus} blocks x 8 waves x {iters} x 8 v_mfma_f32_32x32x16_bf16 on register operands, median of 5",
+            "mfma_package_power": cal_power.result(),
+        }
+        del src, dst, sink
+        log(f"[bench] measured peaks: copy {measured_peak['copy_GB/s']} GB/s, bf16 MFMA {measured_peak['mfma_TFLOP/s']} TFLOP/s")
+        if dt == "bf16":
+            for c in per_call:
+                if "GB/s" in per_call[c]:
+                    per_call[c]["frac_of_measured_copy"] = round(per_call[c]["GB/s"] / measured_peak["copy_GB/s"], 4)
 
     if not args.step_only:
         # the planner (Algorithm 1) on the P x E count matrix of this batch: not one of the timed calls of a step
@@ -288,13 +401,24 @@ def main():
         ptimes = pbuf.times.cpu().numpy()
         per_call["plan"] = {"ms": round(pe[0].elapsed_time(pe[1]) / 20, 4), "in_step": False, "selected": int(info[1]),
                             "kept": int(info[0]), "model_T_before_s": float(ptimes[0]), "model_T_after_s": float(ptimes[1]),
-                            "gating": f"{cfg.P}x{cfg.E} counts, n=1, Eq. 7"}
+                            "gating": f"{cfg.P}x{cfg.E} counts, n=1, Eq. 6"}
         if not args.no_cpu_baseline:
             from oracle import planner_oracle as po
             t0 = time.perf_counter()
             ref = po.greedy_search(gating_np.astype(np.int64), 1, po.PlannerModel(alpha=1.0, overlap=False, **pc))
             per_call["plan"]["oracle_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
             assert ref["cnt"] == int(info[0]) and ref["T_output"] == float(ptimes[1]), "planner disagrees with its oracle"
+            # the ablation's fixed policies (Section 6.4) through the same performance model, and the balance degree
+            # (standard deviation of the per-device load, Section 6.3) without a placement and under each policy
+            m_ = po.PlannerModel(alpha=1.0, overlap=False, **pc)
+            g64 = gating_np.astype(np.int64)
+            H0, R0 = po.loads(g64, po.placement(cfg.P, cfg.E, [], []))
+            comp = {"none": {"model_T_s": float(ptimes[0]), "RB": round(po.balance_degree(H0), 1)},
+                    "greedy (device)": {"model_T_s": float(ptimes[1]), "RB": round(po.balance_degree(pbuf.H.cpu().numpy()), 1)}}
+            for r_top in (2, 3):
+                Ht, Rt = po.loads(g64, po.top_policy(g64, r_top))
+                comp[f"top{r_top}"] = {"model_T_s": po.layer_time(Rt, Ht, r_top, 0, m_), "RB": round(po.balance_degree(Ht), 1)}
+            per_call["plan"]["policies"] = comp
 
         # the rest of the gate's backward (parameter gradients, gate path of the input gradient): beside the step
         if cfg.backward and E <= 64:
@@ -324,12 +448,14 @@ def main():
             pools = [torch.empty(E, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
             slots = [torch.empty(cfg.G_max, d * h, dtype=torch.bfloat16, device=dev) for _ in range(n_t)]
             slot_expert = torch.full((cfg.G_max,), -1, dtype=torch.int32, device=dev)
-            hd.trans(expert_dest, slot_expert, pools, slots)
+            pool_ver = torch.zeros(E, dtype=torch.int32, device=dev)
+            slot_ver = torch.full((cfg.G_max,), -1, dtype=torch.int32, device=dev)
+            hd.trans(expert_dest, slot_expert, pools, slots, pool_ver, slot_ver)
             torch.cuda.synchronize()
             te = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             slot_expert.fill_(-1)
-            te[0].record(); hd.trans(expert_dest, slot_expert, pools, slots); te[1].record()
-            hd.trans(expert_dest, slot_expert, pools, slots); te[2].record()          # nothing to move the second time
+            te[0].record(); hd.trans(expert_dest, slot_expert, pools, slots, pool_ver, slot_ver); te[1].record()
+            hd.trans(expert_dest, slot_expert, pools, slots, pool_ver, slot_ver); te[2].record()   # nothing to move the second time
             torch.cuda.synchronize()
             moved = 2.0 * len(group_rows) * n_t * d * h * es
             ms_all, ms_none = te[0].elapsed_time(te[1]), te[1].elapsed_time(te[2])
@@ -391,16 +517,31 @@ def main():
                                f"hosted groups={len(group_rows)} alpha={wl.alpha_for(cfg, args.iteration)}",
                    "pass": "fwd+bwd" if cfg.backward else "fwd", "hosted_rows_M": M, "assignments_A": A},
         "roofline": {"bound": "mfma" if dt == "bf16" else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(cfg.index),
+                     "frac": achieved / peak, "traffic": measured_traffic(cfg.index, ffn_flops) if dt == "bf16" else None,
                      "kernel": "grouped_gemm_kernel (all launches of expert_ffn_fwd/bwd in a step)",
-                     "flops_per_step": ffn_flops, "ms_per_step": ffn_ms, "package_power": power.result()},
+                     "flops_per_step": ffn_flops, "ms_per_step": ffn_ms,
+                     "median_ms_per_step": float(np.median(ffn_all)), "min_ms_per_step": float(ffn_all.min()),
+                     "frac_at_min": ffn_flops / (float(ffn_all.min()) * 1e-3) / 1e12 / peak,
+                     "package_power": power.result()},
+        "step_ms": {"mean": float(step_all.mean()), "median": float(np.median(step_all)), "min": float(step_all.min()),
+                    "what": "first to last event of a step on the launch stream"},
         "per_call": per_call,
     }
+    result["config"]["act_saved"] = bool(act_saved)
+    if measured_peak is not None:
+        result["roofline"]["measured_peak"] = measured_peak
+        if dt == "bf16":
+            result["roofline"]["frac_of_measured"] = achieved / measured_peak["mfma_TFLOP/s"]
+    gb = ffn_group_bounds(cfg, group_rows, cfg.backward)
+    bound_ms = sum(x["bound_us"] for x in gb) / 1e3
+    result["roofline"]["per_group"] = {"groups": gb, "sum_of_bounds_ms": round(bound_ms, 4),
+                                       "frac_of_bound": round(bound_ms / ffn_ms, 4) if ffn_ms > 0 else None,
+                                       "what": "bound_g = max(flops_g / MFMA peak, bytes_g / HBM peak) at the published peaks"}
     if not args.no_cpu_baseline:
         n_tok = args.cpu_tokens or {0: 512, 1: 1024, 2: 256, 3: 512, 4: 256}[cfg.index]
         n_hid = {0: cfg.h, 1: 64, 2: 32, 3: 64, 4: 32}[cfg.index]
         t0 = time.perf_counter()
-        result["cpu_baseline"] = cpu_baseline(cfg, inp, expert_dest_np, min(n_tok, T), min(n_hid, h))
+        result["cpu_baseline"] = cpu_baseline(cfg, inp, min(n_tok, T), min(n_hid, h))
         log(f"[bench] cpu baseline took {time.perf_counter() - t0:.1f} s")
     print(json.dumps(result), flush=True)
 

@@ -17,7 +17,11 @@
  *     synchronise and never read device data on the host (moe_read_status excepted).
  *   - Arguments are checked on the host before anything is launched.  Return value: MOE_OK or a
  *     negative moe_status_t; on an error nothing has been enqueued.
- *   - Outputs are overwritten, never accumulated into.  Same inputs give the same bits.
+ *   - Outputs are overwritten, never accumulated into (the one exception, moe_expert_ffn_bwd_acc, says so in
+ *     its name and adds to its weight gradients only).  Same inputs give the same bits.
+ *   - A handle is an immutable description of the problem (moe_set_act_saved is its one setting): calls keep
+ *     no state in it between them, so one handle may be used from several threads as long as calls that share
+ *     a workspace do not overlap and moe_set_act_saved is not called while another call is running.
  *   - Row-major everywhere.  "elt" is the activation type of the handle: float (MOE_F32) or
  *     bfloat16 (MOE_BF16, upper half of an IEEE float, round-to-nearest-even).  Gate parameters,
  *     logits, gate weights and weight gradients are always float; indices are int32_t.
@@ -103,8 +107,9 @@ int moe_read_status(moe_handle_t h, const void* ws, void* stream, int* status);
 /* Gate and routing (Section 2.1: the gate relates an input to all experts and routes it to the
  * top-k).  logits[t,e] = bg[e] + sum_c X[t,c] * Wg[c,e] in fp32 with a fixed summation order
  * (two partial sums fed by alternating blocks of 32 columns; inside a block the columns are visited
- * as 8q + j, j = 0..7 outer, q = 0..3 inner, one fused multiply-add each; logit = (s0 + s1) + bias:
- * the order of the fp32 matrix instruction) so that routing is reproducible bit for bit.  idx[t,0..k) = the k largest logits, best
+ * as 8q + j, j = 0..7 outer, q = 0..3 inner, one fused multiply-add each; logit = (s0 + s1) + bias)
+ * so that routing is reproducible bit for bit.  This order is part of the interface: it is frozen, and any
+ * kernel behind this call has to reproduce it.  idx[t,0..k) = the k largest logits, best
  * first, ties to the lowest index, NaN ranked as -inf.  p = softmax(logits[t,:]);
  * w[t,j] = p[idx[t,j]], divided by their sum over j when renorm = 1.
  *   in : X[T,d] elt, Wg[d,E] float, bg[E] float
@@ -120,13 +125,22 @@ int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void*
  * device are computed locally, the others go to the expert's owner; Fig. 2: first all-to-all).
  *   in : expert_dest[E] int32 in [0,P): destination that computes this GPU's inputs of expert e
  *        (== self for owned and replicated experts); X[T,d] elt; idx[A]; counts[E] as returned by
- *        moe_expert_counts for the same idx.  If the call of this handle before this one that used
- *        the routing part of the workspace was a moe_expert_counts of this idx pointer, its per-chunk
- *        histograms are reused (once): idx must not have been rewritten in between
+ *        moe_expert_counts for the same idx
  *   out: every array of *layout (host struct of device pointers); Xp[A,d] elt with
- *        Xp[r,:] = X[perm[r] / k, :] (bit copies) */
+ *        Xp[r,:] = X[perm[r] / k, :] (bit copies)
+ * Uses the workspace (it rebuilds the per-chunk histograms of idx there; nothing is carried over from
+ * earlier calls). */
 int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
                  const int32_t* counts, const moe_layout_t* layout, void* Xp, void* ws, void* stream);
+
+/* As moe_dispatch, for the usual sequence counts -> plan -> dispatch: the caller states that the routing
+ * part of `ws` still holds what moe_expert_counts(h, idx, counts, ws) left there, i.e. that call was made
+ * with this idx, this workspace and a handle of the same T, k and E, idx has not been rewritten since, and
+ * no other moe_expert_counts / moe_dispatch* call has used this workspace in between.  The histograms are
+ * then not rebuilt.  If the statement is false the layout is wrong and no error is reported: when in
+ * doubt call moe_dispatch. */
+int moe_dispatch_after_counts(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                              const int32_t* counts, const moe_layout_t* layout, void* Xp, void* ws, void* stream);
 
 /* Forward expert computation over the hosted groups (Section 4.2, Eq. 2), ragged and possibly
  * empty, without padding:  GELU: Yp = gelu(Xp W1) W2;  SwiGLU: Yp = (silu(Xp W1) * (Xp W3)) W2,
@@ -155,10 +169,21 @@ int moe_combine_bwd(moe_handle_t h, const void* dOut, const void* Yp, const int3
  * dXp = dZ W1^T (+ dU W3^T);  dW1 = Xp^T dZ, dW3 = Xp^T dU, dW2 = A^T dYp, each over the group's rows.
  *   in : dYp[A,d], Xp[A,d], Z[A,h], U[A,h] (SwiGLU) elt; layout; W1, W2, W3 as in the forward call
  *   out: dXp[A,d] elt, rows of hosted groups only; dW1[G,d,h], dW2[G,h,d], dW3[G,d,h] float,
- *        written for all G groups (zeros for an empty or unused group) */
+ *        written for all G groups (zeros for an empty or unused group)
+ * The activation A is not a saved tensor: by default it is recomputed from Z (and U) into the workspace.
+ * See moe_set_act_saved. */
 int moe_expert_ffn_bwd(moe_handle_t h, const void* dYp, const void* Xp, const void* Z, const void* U,
                        const moe_layout_t* layout, const void* W1, const void* W2, const void* W3,
                        void* dXp, float* dW1, float* dW2, float* dW3, void* ws, void* stream);
+
+/* saved = 1: the caller states that, whenever moe_expert_ffn_bwd(_acc) is called with this handle, the
+ * workspace it is given still holds the activation A that moe_expert_ffn_fwd wrote there for the same rows
+ * (same handle shape, same layout, same Xp and weights, and no other call has used that workspace since):
+ * a layer that keeps its workspace from its forward to its backward pass.  The backward pass then reads A
+ * instead of recomputing and rewriting it (a third of the bytes its first contraction writes).  saved = 0
+ * (the default): A is recomputed from Z and U, and the workspace may be shared freely between calls.
+ * MOE_F32 handles ignore the setting. */
+int moe_set_act_saved(moe_handle_t h, int saved);
 
 /* As moe_expert_ffn_bwd, but the weight gradients are added to what dW1, dW2, dW3 hold (all G groups;
  * an empty group adds zero): the form in which a device folds the gradient of a replicated expert into a
@@ -181,13 +206,13 @@ int moe_gate_bwd(moe_handle_t h, const float* dw, const float* logits, const int
 
 /* Gradients of the gate's parameters (the gate network of Section 2.1 is the linear map
  * logit[t,e] = bg[e] + sum_c X[t,c] Wg[c,e]):  dWg[c,e] = sum_t X[t,c] dlogits[t,e],  dbg[e] = sum_t dlogits[t,e].
- * fp32 sums in a fixed order (same bits every run).  E <= 64 (else MOE_ERR_UNIMPLEMENTED).  Uses the workspace.
+ * fp32 sums in a fixed order (same bits every run).  Uses the workspace.
  *   in : X[T,d] elt, dlogits[T,E] float;  out: dWg[d,E] float, dbg[E] float */
 int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, float* dWg, float* dbg,
                         void* ws, void* stream);
 
 /* Complete gradient of the layer input: the backward of the send (as moe_dispatch_bwd) plus the gate
- * path, rounded once:  dX[t,:] = sum_j dXp[pos[t*k+j],:] + sum_e dlogits[t,e] Wg[:,e].  E <= 64.
+ * path, rounded once:  dX[t,:] = sum_j dXp[pos[t*k+j],:] + sum_e dlogits[t,e] Wg[:,e].
  *   in : dXp[A,d] elt, pos[A], dlogits[T,E] float, Wg[d,E] float;  out: dX[T,d] elt */
 int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const float* dlogits, const float* Wg,
                    void* dX, void* stream);
@@ -207,17 +232,35 @@ int moe_recv_layout(moe_handle_t h, const moe_layout_t* local, const int32_t* re
                     void* stream);
 
 /* Trans on one GPU (Section 4.1: the parameters of a selected expert are transferred to the devices that
- * compute its inputs).  With the parameters of all E experts in pools in this GPU's memory, the transfer is
- * a gather of the hosted experts into the G group slots that moe_expert_ffn_fwd/bwd read, driven by the
- * plan as it lies in device memory: group g receives the g-th expert e (ascending) with
- * expert_dest[e] == self.  A slot that already holds that expert is not copied again.
- *   in    : expert_dest[E] int32 (device); n_tensors (1..8) and, on the HOST, arrays of n_tensors device
- *           pointers pools[i] ([E] experts of bytes_per_expert[i] bytes each, a multiple of 16, 16-byte aligned)
- *   in/out: slot_expert[G] int32 (device): the expert each slot holds, -1 for none; updated after the copies
+ * compute its inputs; Section 5.1: an expert's parameters are updated before every such transfer).  With the
+ * parameters of all E experts in pools in this GPU's memory, the transfer is a gather of the hosted experts
+ * into the G group slots that moe_expert_ffn_fwd/bwd read, driven by the plan as it lies in device memory:
+ * group g receives the g-th expert e (ascending) with expert_dest[e] == self.  A slot is not copied again
+ * when it already holds that expert in the pool's current version.
+ *   in    : expert_dest[E] int32 (device); pool_version[E] int32 (device): a number per expert that the caller
+ *           changes whenever it has updated that expert's parameters in the pools (an optimizer step);
+ *           n_tensors (1..8) and, on the HOST, arrays of n_tensors device pointers pools[i] ([E] experts of
+ *           bytes_per_expert[i] bytes each, a multiple of 16, 16-byte aligned)
+ *   in/out: slot_expert[G] int32 (device): the expert each slot holds, -1 for none; slot_version[G] int32
+ *           (device): the version it was copied at; both updated after the copies
  *   out   : groups[i] ([G] slots of bytes_per_expert[i] bytes); slots beyond the hosted experts keep their contents
+ * pool_version and slot_version may both be NULL: then every hosted slot is copied on every call.
  * More hosted experts than G is the caller's error (moe_dispatch reports it through moe_read_status). */
-int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, int n_tensors,
-              const void* const* pools, void* const* groups, const size_t* bytes_per_expert, void* stream);
+int moe_trans(moe_handle_t h, const int32_t* expert_dest, const int32_t* pool_version, int32_t* slot_expert,
+              int32_t* slot_version, int n_tensors, const void* const* pools, void* const* groups,
+              const size_t* bytes_per_expert, void* stream);
+
+/* Agg on one GPU (Section 4.1: the gradients computed for a replicated expert are aggregated where the expert's
+ * parameters live).  The inverse walk of moe_trans: the weight gradient of hosted group g, as moe_expert_ffn_bwd
+ * wrote it, is ADDED to the entry of the g-th expert e (ascending) with expert_dest[e] == self in a pool of
+ * per-expert gradients, so that gradients keep accumulating per expert while the plan, and with it the meaning of
+ * a group slot, changes from one iteration to the next.
+ *   in    : expert_dest[E] int32 (device); n_tensors (1..8) and, on the HOST, arrays of n_tensors device pointers
+ *           group_grads[i] ([G] slots of floats_per_expert[i] floats, a multiple of 4, 16-byte aligned)
+ *   in/out: pool_grads[i] ([E] experts of floats_per_expert[i] floats): pool[e] += group[g]; other experts untouched
+ * Fixed order of additions (one per element): same bits every run. */
+int moe_agg(moe_handle_t h, const int32_t* expert_dest, int n_tensors, const float* const* group_grads,
+            float* const* pool_grads, const size_t* floats_per_expert, void* stream);
 
 /* ---- planner (Sections 4.2-4.3 and 5.3 of the paper) ------------------------------------------
  *
@@ -225,8 +268,8 @@ int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, 
  * GPU, in one wavefront, from the matrix of routing counts of all devices, so that the plan of the
  * next iteration can be produced without the host reading any counts.  A placement is evaluated
  * with the performance model T'(R, H, s, n) = 4 T_A2A(R) + 3 T_FEC(H) + T_Trans(s, n) + T_Agg(s, n)
- * (Eqs. 1-7) or, with overlap = 1, with Trans and Agg reduced by the computation the scheduler hides
- * them behind (Eq. 8); the search runs while max(H) - min(H) >= alpha I / E (Eq. 9).
+ * (Eqs. 1-6) or, with overlap = 1, with Trans and Agg reduced by the computation the scheduler hides
+ * them behind (Eq. 8); the search runs while max(H) - min(H) >= alpha I / E (Eq. 7).
  *
  * Where Algorithm 1 is silent: loads are computed before the first evaluation; expert e belongs to
  * device e / (E/D); the heaviest device (ties: lowest index) contributes its unselected expert with
@@ -238,8 +281,8 @@ int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, 
 typedef struct {
     int D, E;                   /* devices, experts; 1 <= D <= 64, E <= 1024, E % D == 0 */
     int n;                      /* devices a selected expert is not transferred to, 0 <= n <= D-1 */
-    int overlap;                /* 0: Eq. 7;  1: Eq. 8 */
-    double alpha;               /* coefficient of the balance test, Eq. 9 */
+    int overlap;                /* 0: Eq. 6;  1: Eq. 8 */
+    double alpha;               /* coefficient of the balance test, Eq. 7 */
     double size_input;          /* bytes of one input */
     double size_params;         /* bytes of one expert's parameters */
     double size_grads;          /* bytes of one expert's gradients */
@@ -270,6 +313,17 @@ typedef struct {
  * out: see moe_plan_out_t (struct on the host, pointers to device memory).
  * Errors: MOE_ERR_NULL, MOE_ERR_SHAPE (sizes, n, non-positive or non-finite model constants). */
 int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out_t* out, void* stream);
+
+/* ---- calibration (for the benchmark; nothing of the layer's path calls these) -----------------------------
+ * moe_calib_copy: dst[0..bytes) = src[0..bytes) by a plain streaming kernel (device pointers, 16-byte aligned,
+ * bytes a multiple of 16): what a copy sustains on this GPU, to set beside the published HBM bandwidth.
+ * moe_calib_mfma: one block of 8 wavefronts per compute unit, every wavefront issues iters x 8 bf16 32x32x16
+ * matrix instructions (32768 flop each) on operands held in registers: what the matrix cores sustain at this
+ * GPU's power limit, to set beside the published peak.  out: device, out_floats floats of which the first
+ * blocks x threads are written (so that the work cannot be optimised away; MOE_ERR_SHAPE if there are fewer:
+ * 512 per compute unit are enough); *blocks and *threads (host) receive the launch shape. */
+int moe_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
+int moe_calib_mfma(float* out, size_t out_floats, int iters, int* blocks, int* threads, void* stream);
 
 #ifdef __cplusplus
 }

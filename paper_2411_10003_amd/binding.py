@@ -25,6 +25,7 @@ EXPORTS = [
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
     "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans", "moe_recv_layout",
+    "moe_dispatch_after_counts", "moe_set_act_saved", "moe_agg", "moe_calib_copy", "moe_calib_mfma",
 ]
 
 
@@ -72,6 +73,8 @@ def load() -> ctypes.CDLL:
         lib.moe_gate_topk.argtypes = [vp] * 8
         lib.moe_expert_counts.argtypes = [vp] * 5
         lib.moe_dispatch.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(_Layout), vp, vp, vp]
+        lib.moe_dispatch_after_counts.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(_Layout), vp, vp, vp]
+        lib.moe_set_act_saved.argtypes = [vp, ip]
         lib.moe_expert_ffn_fwd.argtypes = [vp, vp, ctypes.POINTER(_Layout)] + [vp] * 8
         lib.moe_combine.argtypes = [vp] * 6
         lib.moe_combine_bwd.argtypes = [vp] * 8
@@ -81,7 +84,10 @@ def load() -> ctypes.CDLL:
         lib.moe_gate_bwd.argtypes = [vp] * 6
         lib.moe_gate_bwd_params.argtypes = [vp] * 7
         lib.moe_input_grad.argtypes = [vp] * 7
-        lib.moe_trans.argtypes = [vp, vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
+        lib.moe_trans.argtypes = [vp, vp, vp, vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
+        lib.moe_agg.argtypes = [vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
+        lib.moe_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.moe_calib_mfma.argtypes = [vp, ctypes.c_size_t, ip, ctypes.POINTER(ip), ctypes.POINTER(ip), vp]
         lib.moe_recv_layout.argtypes = [vp, ctypes.POINTER(_Layout), vp, ctypes.POINTER(_Layout), vp]
         lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
@@ -131,6 +137,26 @@ def plan(gating: torch.Tensor, out: PlanBuffers, *, n: int, overlap: bool, alpha
     rc = lib.moe_plan(ctypes.byref(cfg), g, ctypes.byref(out.c), _stream())
     if rc != 0:
         raise MoeError(rc, "moe_plan", lib.moe_status_string(rc).decode())
+
+
+def calib_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """moe_calib_copy: a plain streaming copy of src into dst (uint8 tensors of the same size)."""
+    lib = load()
+    n = src.numel() * src.element_size()
+    rc = lib.moe_calib_copy(_ptr(src, src.dtype, src.numel(), "src"), _ptr(dst, src.dtype, src.numel(), "dst"), n, _stream())
+    if rc != 0:
+        raise MoeError(rc, "moe_calib_copy", lib.moe_status_string(rc).decode())
+
+
+def calib_mfma(out: torch.Tensor, iters: int) -> float:
+    """moe_calib_mfma: enqueue the register-only bf16 MFMA loop; returns the flops it performs."""
+    lib = load()
+    blocks, threads = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib.moe_calib_mfma(_ptr(out, torch.float32, 1, "out"), out.numel(), int(iters), ctypes.byref(blocks),
+                            ctypes.byref(threads), _stream())
+    if rc != 0:
+        raise MoeError(rc, "moe_calib_mfma", lib.moe_status_string(rc).decode())
+    return float(blocks.value) * (threads.value // 64) * iters * 8 * 32768.0
 
 
 class Layout:
@@ -211,12 +237,20 @@ class Handle:
         self._check(self.lib.moe_expert_counts(self._h, _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"),
                                                self._ws(), _stream()), "moe_expert_counts")
 
-    def dispatch(self, expert_dest, X, idx, counts, layout: Layout, Xp):
+    def dispatch(self, expert_dest, X, idx, counts, layout: Layout, Xp, after_counts: bool = False):
         i32 = torch.int32
-        self._check(self.lib.moe_dispatch(
+        fn = self.lib.moe_dispatch_after_counts if after_counts else self.lib.moe_dispatch
+        self._check(fn(
             self._h, _ptr(expert_dest, i32, self.E, "expert_dest"), _ptr(X, self.elt, self.T * self.d, "X"),
             _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"), ctypes.byref(layout.c),
-            _ptr(Xp, self.elt, self.A * self.d, "Xp"), self._ws(), _stream()), "moe_dispatch")
+            _ptr(Xp, self.elt, self.A * self.d, "Xp"), self._ws(), _stream()),
+            "moe_dispatch_after_counts" if after_counts else "moe_dispatch")
+
+    def dispatch_after_counts(self, expert_dest, X, idx, counts, layout: Layout, Xp):
+        self.dispatch(expert_dest, X, idx, counts, layout, Xp, after_counts=True)
+
+    def set_act_saved(self, saved: bool):
+        self._check(self.lib.moe_set_act_saved(self._h, int(bool(saved))), "moe_set_act_saved")
 
     def expert_ffn_fwd(self, Xp, layout: Layout, W1, W2, W3, Yp, Z, U):
         e, dh = self.elt, self.G * self.d * self.h
@@ -261,7 +295,7 @@ class Handle:
             self._h, _ptr(dw, f32, self.A, "dw"), _ptr(logits, f32, self.T * self.E, "logits"),
             _ptr(idx, torch.int32, self.A, "idx"), _ptr(dlogits, f32, self.T * self.E, "dlogits"), _stream()), "moe_gate_bwd")
 
-    def trans(self, expert_dest, slot_expert, pools, groups):
+    def trans(self, expert_dest, slot_expert, pools, groups, pool_version=None, slot_version=None):
         """moe_trans: gather the hosted experts' tensors from the pools into the group slots."""
         n = len(pools)
         per = [p.numel() // self.E * p.element_size() for p in pools]
@@ -274,8 +308,24 @@ class Handle:
         ga = (ctypes.c_void_p * n)(*(g.data_ptr() for g in groups))
         ba = (ctypes.c_size_t * n)(*per)
         self._check(self.lib.moe_trans(
-            self._h, _ptr(expert_dest, torch.int32, self.E, "expert_dest"), _ptr(slot_expert, torch.int32, self.G, "slot_expert"),
+            self._h, _ptr(expert_dest, torch.int32, self.E, "expert_dest"), _ptr(pool_version, torch.int32, self.E, "pool_version"),
+            _ptr(slot_expert, torch.int32, self.G, "slot_expert"), _ptr(slot_version, torch.int32, self.G, "slot_version"),
             n, pa, ga, ba, _stream()), "moe_trans")
+
+    def agg(self, expert_dest, group_grads, pool_grads):
+        """moe_agg: add the hosted groups' weight gradients to the per-expert gradient pools."""
+        n = len(group_grads)
+        per = [p.numel() // self.E for p in pool_grads]
+        for p, g, b in zip(pool_grads, group_grads, per):
+            if not (p.is_cuda and g.is_cuda and p.is_contiguous() and g.is_contiguous()):
+                raise ValueError("agg: need contiguous device tensors")
+            if p.dtype != torch.float32 or g.dtype != torch.float32 or p.numel() % self.E or g.numel() < self.G * b:
+                raise ValueError("agg: pool / group sizes or dtypes do not match")
+        ga = (ctypes.c_void_p * n)(*(g.data_ptr() for g in group_grads))
+        pa = (ctypes.c_void_p * n)(*(p.data_ptr() for p in pool_grads))
+        ba = (ctypes.c_size_t * n)(*per)
+        self._check(self.lib.moe_agg(self._h, _ptr(expert_dest, torch.int32, self.E, "expert_dest"), n, ga, pa, ba, _stream()),
+                    "moe_agg")
 
     def recv_layout(self, local: Layout, recv_offsets, out: Layout):
         self._check(self.lib.moe_recv_layout(
@@ -330,7 +380,7 @@ def layer_forward(hd: Handle, b: LayerBuffers, X, Wg, bg, expert_dest, W1, W2, W
     """The forward calls in order; rows of other destinations in b.Yp are left as the caller set them."""
     hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w)
     hd.expert_counts(b.idx, b.counts)
-    hd.dispatch(expert_dest, X, b.idx, b.counts, b.layout, b.Xp)
+    hd.dispatch_after_counts(expert_dest, X, b.idx, b.counts, b.layout, b.Xp)   # same idx, same workspace, nothing in between
     hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z, b.U)
     hd.combine(b.Yp, b.layout.pos, b.w, b.out)
 

@@ -56,6 +56,8 @@ struct Carve {
 
 }  // namespace
 
+int moe_hip_status(hipError_t e) { return hip_status(e); }
+
 extern "C" {
 
 int moe_create(moe_handle_t* out, const moe_shape_t* shape)
@@ -141,13 +143,12 @@ int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void*
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
     if (e == hipSuccess) e = launch_counts_from_hist(h->s, c.chunk_hist(), h->n_chunks, counts, st);
-    h->hist_idx = (e == hipSuccess) ? idx : nullptr;
-    h->hist_ws = ws;
     return hip_status(e);
 }
 
-int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
-                 const int32_t* counts, const moe_layout_t* L, void* Xp, void* ws, void* stream)
+// fresh_hist: the per-chunk histograms of this idx are already in the workspace (the caller says so)
+static int dispatch_impl(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                         const int32_t* counts, const moe_layout_t* L, void* Xp, void* ws, void* stream, bool fresh_hist)
 {
     if (!h || !expert_dest || !X || !idx || !counts || !L || !Xp) return MOE_ERR_NULL;
     if (!L->slot_of_expert || !L->slot_offsets || !L->dest_offsets || !L->dest_slots || !L->pos || !L->perm)
@@ -155,10 +156,8 @@ int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, cons
     if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
     const Carve c{(char*)ws, h};
     hipStream_t st = (hipStream_t)stream;
-    // the per-chunk histograms of moe_expert_counts are still in the workspace when that call counted this idx
     hipError_t e = hipSuccess;
-    if (h->hist_idx != idx || h->hist_ws != ws) e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
-    h->hist_idx = nullptr;                                // good for one dispatch
+    if (!fresh_hist) e = launch_chunk_hist(h->s, idx, c.chunk_hist(), h->n_chunks, st);
     if (e == hipSuccess && layout_positions_fusable(h->s, h->n_chunks)) {
         e = launch_layout_positions(h->s, idx, expert_dest, counts, c.chunk_hist(), h->n_chunks, *L, c.status(), st);
     } else {
@@ -168,6 +167,26 @@ int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, cons
     }
     if (e == hipSuccess) e = launch_scatter_rows(h->s, X, L->pos, Xp, st);
     return hip_status(e);
+}
+
+int moe_dispatch(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                 const int32_t* counts, const moe_layout_t* L, void* Xp, void* ws, void* stream)
+{
+    return dispatch_impl(h, expert_dest, X, idx, counts, L, Xp, ws, stream, false);
+}
+
+int moe_dispatch_after_counts(moe_handle_t h, const int32_t* expert_dest, const void* X, const int32_t* idx,
+                              const int32_t* counts, const moe_layout_t* L, void* Xp, void* ws, void* stream)
+{
+    return dispatch_impl(h, expert_dest, X, idx, counts, L, Xp, ws, stream, true);
+}
+
+int moe_set_act_saved(moe_handle_t h, int saved)
+{
+    if (!h) return MOE_ERR_NULL;
+    if (saved != 0 && saved != 1) return MOE_ERR_SHAPE;
+    h->act_saved = saved;
+    return MOE_OK;
 }
 
 int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* L,
@@ -218,6 +237,7 @@ static int ffn_bwd_impl(moe_handle_t h, const void* dYp, const void* Xp, const v
     a.dYp = dYp; a.dXp = dXp; a.dZ = c.dz(); a.dU = c.du();
     a.dW1 = dW1; a.dW2 = dW2; a.dW3 = dW3;
     a.accumulate = accumulate; a.split_ws = c.split();
+    a.act_saved = h->act_saved != 0;
     hipStream_t st = (hipStream_t)stream;
     return hip_status(h->s.dtype == MOE_F32 ? launch_ffn_bwd_f32(h->s, a, st) : launch_ffn_bwd_bf16(h->s, a, st));
 }
@@ -253,7 +273,6 @@ int moe_gate_bwd_params(moe_handle_t h, const void* X, const float* dlogits, flo
 {
     if (!h || !X || !dlogits || !dWg || !dbg) return MOE_ERR_NULL;
     if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
-    if (h->s.E > 64) return MOE_ERR_UNIMPLEMENTED;
     const Carve c{(char*)ws, h};
     float* part = c.gate_part();
     float* part_b = part + (size_t)gate_grad_partitions(h->s) * h->s.d * h->s.E;
@@ -264,14 +283,15 @@ int moe_input_grad(moe_handle_t h, const void* dXp, const int32_t* pos, const fl
                    void* dX, void* stream)
 {
     if (!h || !dXp || !pos || !dlogits || !Wg || !dX) return MOE_ERR_NULL;
-    if (h->s.E > 64) return MOE_ERR_UNIMPLEMENTED;
     return hip_status(launch_input_grad(h->s, dXp, pos, dlogits, Wg, dX, (hipStream_t)stream));
 }
 
-int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, int n_tensors,
-              const void* const* pools, void* const* groups, const size_t* bytes_per_expert, void* stream)
+int moe_trans(moe_handle_t h, const int32_t* expert_dest, const int32_t* pool_version, int32_t* slot_expert,
+              int32_t* slot_version, int n_tensors, const void* const* pools, void* const* groups,
+              const size_t* bytes_per_expert, void* stream)
 {
     if (!h || !expert_dest || !slot_expert || !pools || !groups || !bytes_per_expert) return MOE_ERR_NULL;
+    if ((pool_version == nullptr) != (slot_version == nullptr)) return MOE_ERR_NULL;       // both or neither
     if (n_tensors < 1 || n_tensors > 8) return MOE_ERR_SHAPE;
     for (int i = 0; i < n_tensors; ++i) {
         if (!pools[i] || !groups[i]) return MOE_ERR_NULL;
@@ -281,8 +301,25 @@ int moe_trans(moe_handle_t h, const int32_t* expert_dest, int32_t* slot_expert, 
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     for (int i = 0; i < n_tensors && e == hipSuccess; ++i)
-        e = launch_trans_gather(h->s, expert_dest, slot_expert, pools[i], groups[i], (long)bytes_per_expert[i], st);
-    if (e == hipSuccess) e = launch_trans_commit(h->s, expert_dest, slot_expert, st);
+        e = launch_trans_gather(h->s, expert_dest, pool_version, slot_expert, slot_version, pools[i], groups[i],
+                                (long)bytes_per_expert[i], st);
+    if (e == hipSuccess) e = launch_trans_commit(h->s, expert_dest, pool_version, slot_expert, slot_version, st);
+    return hip_status(e);
+}
+
+int moe_agg(moe_handle_t h, const int32_t* expert_dest, int n_tensors, const float* const* group_grads,
+            float* const* pool_grads, const size_t* floats_per_expert, void* stream)
+{
+    if (!h || !expert_dest || !group_grads || !pool_grads || !floats_per_expert) return MOE_ERR_NULL;
+    if (n_tensors < 1 || n_tensors > 8) return MOE_ERR_SHAPE;
+    for (int i = 0; i < n_tensors; ++i) {
+        if (!group_grads[i] || !pool_grads[i]) return MOE_ERR_NULL;
+        if (floats_per_expert[i] == 0 || floats_per_expert[i] % 4 != 0) return MOE_ERR_SHAPE;
+        if ((reinterpret_cast<uintptr_t>(group_grads[i]) | reinterpret_cast<uintptr_t>(pool_grads[i])) & 15) return MOE_ERR_SHAPE;
+    }
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < n_tensors && e == hipSuccess; ++i)
+        e = launch_agg_add(h->s, expert_dest, group_grads[i], pool_grads[i], (long)floats_per_expert[i], (hipStream_t)stream);
     return hip_status(e);
 }
 

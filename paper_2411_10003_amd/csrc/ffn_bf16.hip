@@ -55,6 +55,7 @@ struct GemmParams {
     int accumulate;              // EPI_F32: add to the output instead of overwriting it
     long ldo, o_group_stride;
     const bf16_t *Zin, *Uin;     // BWD1: saved pre-activations
+    int write_act;               // BWD1: recompute the activation into O2 (0: the forward pass's copy is still there)
     float* split_ws;             // NN/NT: partial tiles of the K-split last round, [unit][wave][128 registers][64 lanes]
     int split_cap;               // units that fit there
 };
@@ -618,9 +619,13 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 float z[8], dz[8], a[8];
                 unpack8(zin[pass - pb], z);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { dz[e] = v[e] * gelu_grad_f(z[e]); a[e] = gelu_f(z[e]); }
+                for (int e = 0; e < 8; ++e) dz[e] = v[e] * gelu_grad_f(z[e]);
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
-                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                if (p.write_act) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) a[e] = gelu_f(z[e]);
+                    *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                }
             } else if (EPI == EPI_BWD1_SWIGLU) {
                 float z[8], uu[8], dz[8], du[8], a[8];
                 unpack8(zin[pass - pb], z);
@@ -634,7 +639,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 }
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
                 *reinterpret_cast<uint4*>(p.O1 + o) = pack8(du);
-                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                if (p.write_act) *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             }
         }
         }
@@ -658,24 +663,26 @@ hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st
         p.n_tiles = p.row_tiles * p.col_tiles;
     }
     if (p.n_tiles == 0) return hipSuccess;
-    static int cus = 0;                  // persistent: one block per CU (LDS allows no more), a multiple of 8
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
-            n = 256;
-        cus = n / 8 * 8;
-    }
-    const int grid = cus;
+    // persistent: one block per CU (LDS allows no more), a multiple of 8.  The CU count and the kernels' dynamic
+    // LDS limit are looked up / set once per device (per instantiation).
+    static PerDeviceOnce once;
+    static std::atomic<int> cus_of[64];
+    const int dev = current_device();
+    int cus = (dev >= 0 && dev < 64) ? cus_of[dev].load(std::memory_order_acquire) : 0;
     auto kern = grouped_gemm_kernel<KIND, EPI, false>;
     auto kern_fin = grouped_gemm_kernel<KIND, EPI, KIND != KIND_TN>;     // TN has no split round
-    static bool configured = false;      // per instantiation
-    if (!configured) {
+    if (!once.is_done(dev) || cus == 0) {
+        int n = 0;
+        if (dev < 0 || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cus = n / 8 * 8;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
         if (e == hipSuccess && KIND != KIND_TN)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_fin), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_BYTES);
         if (e != hipSuccess) return e;
-        configured = true;
+        if (dev >= 0 && dev < 64) cus_of[dev].store(cus, std::memory_order_release);
+        once.mark(dev);
     }
+    const int grid = cus;
     // short contractions gain less from the split than the second launch costs
     if (KIND == KIND_TN || p.n_seg * (p.Kseg / BK) < 128) p.split_ws = nullptr;
     p.split_cap = SPLIT_UNITS;
@@ -739,6 +746,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
             p.lda = d; p.ldb = d; p.b_group_stride = d * h; p.Kseg = s.d; p.N = s.h;
             p.O0 = (bf16_t*)a.dZ; p.O1 = (bf16_t*)a.dU; p.O2 = (bf16_t*)a.Act; p.ldo = h;
             p.Zin = (const bf16_t*)a.Z; p.Uin = (const bf16_t*)a.U;
+            p.write_act = a.act_saved ? 0 : 1;
             e = swiglu ? launch<KIND_NT, EPI_BWD1_SWIGLU>(p, A, s.G, st)
                        : launch<KIND_NT, EPI_BWD1_GELU>(p, A, s.G, st);
             if (e != hipSuccess) return e;

@@ -525,13 +525,14 @@ hipError_t run_gate_dma(const moe_shape_t& s, const void* X, const float* Wg, co
     const size_t lds = (size_t)GATE_XRING + (size_t)GATE_NW * 4096 * NT + (route ? (size_t)GATE_TOK * e_pitch * sizeof(float) : 0);
     auto kr = gate_mfma_dma_kernel<NT, true>;
     auto kn = gate_mfma_dma_kernel<NT, false>;
-    static bool configured = false;
-    if (!configured) {
+    static PerDeviceOnce once;                             // per instantiation
+    const int dev = current_device();
+    if (!once.is_done(dev)) {
         const int most = GATE_XRING + GATE_NW * 4096 * NT + GATE_TOK * (16 * NT + 1) * (int)sizeof(float);
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kr), hipFuncAttributeMaxDynamicSharedMemorySize, most);
         if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(kn), hipFuncAttributeMaxDynamicSharedMemorySize, most);
         if (e != hipSuccess) return e;
-        configured = true;
+        once.mark(dev);
     }
     if (route) {
         hipLaunchKernelGGL(kr, dim3(grid), dim3(GATE_THREADS), lds, st, (const bf16_t*)X, Wg, bg, logits, idx, w,

@@ -5,7 +5,8 @@
 // The first sum of dX is the backward of the send (the fourth all-to-all of the performance model,
 // Section 4.2); fusing the gate path into it saves a pass over dX.  Both kernels are bound by HBM
 // (they stream X or dXp once) with E fp32 multiply-adds per element beside it (on the fp32 MFMA for the
-// parameter gradients, where they form a dense contraction over the tokens); fp32 throughout, E <= 64.
+// parameter gradients, where they form a dense contraction over the tokens); fp32 throughout.  More than 64
+// experts are taken in passes (parameter gradients) or chunks (input gradient) of 64.
 #include "internal.h"
 
 #include <type_traits>
@@ -233,8 +234,9 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 template <typename ET, int VN, int NE, int CS>
 __global__ __launch_bounds__(256) void gate_wgrad_mfma_kernel(
     const ET* __restrict__ X, const float* __restrict__ dlogits, float* __restrict__ partial,
-    float* __restrict__ partial_b, int T, int d, int E, int tok_per_part)
+    float* __restrict__ partial_b, int T, int d, int E, int tok_per_part, int e0)
 {
+    // e0: first expert of this pass (more than 64 experts are taken in passes of 16 NE)
     constexpr int SW = 16 * VN;                                    // columns of one strip
     constexpr int NACC = CS * VN * NE;                             // 16 x 16 accumulators of a wave
     typedef typename std::conditional<sizeof(ET) == 2, uint4, float4>::type raw_t;
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256) void gate_wgrad_mfma_kernel(
             const bool tv = t < t_end;
 #pragma unroll
             for (int n = 0; n < NE; ++n) {
-                const int e = n * 16 + li;
+                const int e = e0 + n * 16 + li;
                 dl[u][n] = (tv && e < E) ? dlogits[(size_t)t * E + e] : 0.0f;
             }
 #pragma unroll
@@ -353,13 +355,13 @@ __global__ __launch_bounds__(256) void gate_wgrad_mfma_kernel(
                 for (int n = 0; n < NE; ++n)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int c = c0 + s * SW + (4 * lk + r) * VN + j, e = n * 16 + li;
+                        const int c = c0 + s * SW + (4 * lk + r) * VN + j, e = e0 + n * 16 + li;
                         if (c < d && e < E) partial[((size_t)part * d + c) * E + e] = acc[s][j][n][r];
                     }
         if (blockIdx.x == 0 && lane < 16)
 #pragma unroll
             for (int n = 0; n < NE; ++n)
-                if (n * 16 + lane < E) partial_b[(size_t)part * E + n * 16 + lane] = accb[n];
+                if (e0 + n * 16 + lane < E) partial_b[(size_t)part * E + e0 + n * 16 + lane] = accb[n];
     }
 }
 
@@ -369,9 +371,13 @@ hipError_t launch_wgrad_mfma_t(const moe_shape_t& s, const void* X, const float*
 {
     const int cw = CS * 16 * VN;
     const dim3 grid((s.d + cw - 1) / cw, n_part);
-    hipLaunchKernelGGL((gate_wgrad_mfma_kernel<ET, VN, NE, CS>), grid, dim3(256), 0, st, (const ET*)X, dlogits, partial,
-                       partial_b, s.T, s.d, s.E, tok_per_part);
-    return hipGetLastError();
+    for (int e0 = 0; e0 < s.E; e0 += 16 * NE) {                    // one pass unless E > 64
+        hipLaunchKernelGGL((gate_wgrad_mfma_kernel<ET, VN, NE, CS>), grid, dim3(256), 0, st, (const ET*)X, dlogits, partial,
+                           partial_b, s.T, s.d, s.E, tok_per_part, e0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 __global__ void gate_wgrad_reduce_kernel(const float* __restrict__ partial, const float* __restrict__ partial_b,
@@ -398,6 +404,92 @@ __global__ void gate_wgrad_reduce_kernel(const float* __restrict__ partial, cons
     }
 }
 
+// ---- the same for more than 64 experts ---------------------------------------------------------------
+// The strip of Wg no longer fits LDS at once, so it is staged in chunks of 64 experts and the accumulators
+// must outlive the chunks: a wave keeps U tokens (U x VN sums per lane) for the whole block, the block stages
+// each chunk once and its 4 U tokens use it.  Expert path first (j ascending), then the gate path in
+// ascending e, one rounding at the end.
+template <typename ET, int VN>
+__global__ __launch_bounds__(256) void input_grad_wide_kernel(
+    const ET* __restrict__ dXp, const int32_t* __restrict__ pos, const float* __restrict__ dlogits,
+    const float* __restrict__ Wg, ET* __restrict__ dX, int T, int d, int E, int k)
+{
+    constexpr int CW = 64 * VN, WP = CW + 4, U = 8, EC = 64;
+    __shared__ __attribute__((aligned(16))) float wt[EC * WP];     // [expert of the chunk][column of the strip]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c0 = blockIdx.x * CW, col = c0 + lane * VN;
+    const int t0 = (blockIdx.y * 4 + wave) * U;
+    float acc[U][VN];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) acc[u][i] = 0.0f;
+        const int t = t0 + u;
+        if (t >= T || col >= d) continue;
+        for (int j = 0; j < k; ++j) {
+            const ET* src = dXp + (size_t)pos[(size_t)t * k + j] * d + col;
+            float f[VN];
+            if constexpr (sizeof(ET) == 2) {
+                unpack_bf16x8(*reinterpret_cast<const uint4*>(src), f);
+            } else {
+                const float4 v = *reinterpret_cast<const float4*>(src);
+                f[0] = v.x; f[1] = v.y; f[2 % VN] = v.z; f[3 % VN] = v.w;
+            }
+#pragma unroll
+            for (int i = 0; i < VN; ++i) acc[u][i] += f[i];
+        }
+    }
+    for (int ec0 = 0; ec0 < E; ec0 += EC) {
+        __syncthreads();                                           // everyone is done with the previous chunk
+        for (int i = tid; i < CW * EC; i += 256) {
+            const int c = i / EC, e = i - c * EC;
+            wt[e * WP + c] = (c0 + c < d && ec0 + e < E) ? Wg[(size_t)(c0 + c) * E + ec0 + e] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u;
+            if (t >= T) continue;                                  // uniform per wave
+            const float gl = (ec0 + lane < E) ? dlogits[(size_t)t * E + ec0 + lane] : 0.0f;
+            for (int e = 0; e < EC; ++e) {
+                const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gl), e));
+                if (g == 0.0f) continue;
+                const float* wrow = wt + e * WP + lane * VN;
+#pragma unroll
+                for (int i = 0; i < VN; i += 4) {
+                    const float4 wv = *reinterpret_cast<const float4*>(wrow + i);
+                    acc[u][i + 0] = fmaf(g, wv.x, acc[u][i + 0]); acc[u][i + 1] = fmaf(g, wv.y, acc[u][i + 1]);
+                    acc[u][i + 2] = fmaf(g, wv.z, acc[u][i + 2]); acc[u][i + 3] = fmaf(g, wv.w, acc[u][i + 3]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int t = t0 + u;
+        if (t >= T || col >= d) continue;
+        if constexpr (sizeof(ET) == 2) {
+            *reinterpret_cast<uint4*>(dX + (size_t)t * d + col) =
+                make_uint4(pack_bf16x2(acc[u][0], acc[u][1]), pack_bf16x2(acc[u][2], acc[u][3]),
+                           pack_bf16x2(acc[u][4 % VN], acc[u][5 % VN]), pack_bf16x2(acc[u][6 % VN], acc[u][7 % VN]));
+        } else {
+            *reinterpret_cast<float4*>(dX + (size_t)t * d + col) = make_float4(acc[u][0], acc[u][1], acc[u][2], acc[u][3]);
+        }
+    }
+}
+
+template <typename ET, int VN>
+hipError_t launch_input_grad_wide_t(const moe_shape_t& s, const void* dXp, const int32_t* pos, const float* dlogits,
+                                    const float* Wg, void* dX, hipStream_t st)
+{
+    constexpr int CW = 64 * VN, TOK = 4 * 8;
+    const dim3 grid((s.d + CW - 1) / CW, (s.T + TOK - 1) / TOK);
+    hipLaunchKernelGGL((input_grad_wide_kernel<ET, VN>), grid, dim3(256), 0, st, (const ET*)dXp, pos, dlogits, Wg, (ET*)dX,
+                       s.T, s.d, s.E, s.k);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 int gate_grad_partitions(const moe_shape_t& s) { return s.T < 32 * 256 ? (s.T + 255) / 256 : 32; }
@@ -410,11 +502,12 @@ hipError_t launch_input_grad_t(const moe_shape_t& s, const void* dXp, const int3
     const dim3 grid((s.d + CW - 1) / CW, (s.T + TOK - 1) / TOK);
     const size_t lds = (size_t)s.E * (CW + 4) * sizeof(float);
     auto kern = input_grad_kernel<ET, VN, EC>;
-    static bool configured = false;      // per instantiation
-    if (!configured) {
+    static PerDeviceOnce once;           // per instantiation
+    const int dev = current_device();
+    if (!once.is_done(dev)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * (CW + 4) * 4);
         if (e != hipSuccess) return e;
-        configured = true;
+        once.mark(dev);
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, (const ET*)dXp, pos, dlogits, Wg, (ET*)dX, s.T, s.d, s.E, s.k, TOK);
     return hipGetLastError();
@@ -439,6 +532,8 @@ hipError_t launch_input_grad(const moe_shape_t& s, const void* dXp, const int32_
                              const float* Wg, void* dX, hipStream_t st)
 {
     const bool bf = s.dtype == MOE_BF16;
+    if (s.E > 64) return bf ? launch_input_grad_wide_t<bf16_t, 8>(s, dXp, pos, dlogits, Wg, dX, st)
+                            : launch_input_grad_wide_t<float, 4>(s, dXp, pos, dlogits, Wg, dX, st);
 #ifndef IG_VALU
     if (s.E <= 16) return bf ? launch_input_grad_mfma_t<bf16_t, 8, 1, 1>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_mfma_t<float, 4, 1, 2>(s, dXp, pos, dlogits, Wg, dX, st);
     if (s.E <= 32) return bf ? launch_input_grad_mfma_t<bf16_t, 8, 2, 1>(s, dXp, pos, dlogits, Wg, dX, st) : launch_input_grad_mfma_t<float, 4, 2, 2>(s, dXp, pos, dlogits, Wg, dX, st);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <atomic>
 
 #include "../../include/moehot.h"
 
@@ -20,15 +21,26 @@ struct moe_ctx {
     size_t off_split;      // float [SPLIT_UNITS][256*256] partial tiles of the grouped GEMM's last, K-split round (bf16 path)
     size_t ws_bytes;
     int n_chunks;          // ceil(A / ROUTE_CHUNK)
-    // per-chunk histograms left in a workspace by the last moe_expert_counts: whose they are
-    const void* hist_idx = nullptr;
-    const void* hist_ws = nullptr;
+    // apart from this setting (moe_set_act_saved) a handle is immutable: every call is a function of its arguments
+    int act_saved = 0;     // backward may read the activation the forward pass left in the workspace
 };
+
+// One-time set-up of a kernel per device (its dynamic LDS limit, the device's CU count).  The set-up
+// calls are idempotent, so threads that race simply both make them; devices past 63 are set up on every call.
+struct PerDeviceOnce {
+    std::atomic<uint64_t> done{0};
+    bool is_done(int dev) const { return dev >= 0 && dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1u); }
+    void mark(int dev) { if (dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release); }
+};
+inline int current_device() { int d = 0; if (hipGetDevice(&d) != hipSuccess) d = -1; return d; }
 
 // Assignments handled by one wave of the routing kernels.
 constexpr int ROUTE_CHUNK = 256;
 
 typedef uint16_t bf16_t;  // storage only
+
+// MOE_OK, or MOE_ERR_HIP with the error remembered for moe_last_hip_error() (per thread).
+int moe_hip_status(hipError_t e);
 
 // ---- launchers (each returns a hipError_t; they enqueue on `st`) ----------------------------
 hipError_t launch_gate_topk(const moe_shape_t& s, const void* X, const float* Wg, const float* bg,
@@ -56,9 +68,13 @@ hipError_t launch_input_grad(const moe_shape_t& s, const void* dXp, const int32_
                              const float* Wg, void* dX, hipStream_t st);
 hipError_t launch_gate_wgrad(const moe_shape_t& s, const void* X, const float* dlogits, float* partial, float* partial_b,
                              float* dWg, float* dbg, hipStream_t st);
-hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* slot_expert,
+hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* pool_version,
+                               const int32_t* slot_expert, const int32_t* slot_version,
                                const void* pool, void* groups, long bytes_per_expert, hipStream_t st);
-hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, int32_t* slot_expert, hipStream_t st);
+hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* pool_version,
+                               int32_t* slot_expert, int32_t* slot_version, hipStream_t st);
+hipError_t launch_agg_add(const moe_shape_t& s, const int32_t* expert_dest, const float* groups, float* pool,
+                          long floats_per_expert, hipStream_t st);
 hipError_t launch_recv_layout(const moe_shape_t& s, const int32_t* local_dest_slots, const int32_t* recv_offsets,
                               int32_t* slot_offsets, int32_t* dest_slots, hipStream_t st);
 hipError_t launch_plan(const moe_planner_t& cfg, const int32_t* gating, const moe_plan_out_t& out, hipStream_t st);
@@ -73,6 +89,7 @@ struct ffn_args {
     void *dXp, *dZ, *dU;               // dZ, dU in workspace
     float *dW1, *dW2, *dW3;
     bool accumulate = false;           // weight gradients are added to what dW holds instead of overwriting it
+    bool act_saved = false;            // backward: Act still holds the forward pass's activation (not recomputed)
     float* split_ws = nullptr;         // workspace for K-split partial tiles (SPLIT_UNITS tiles of 256 x 256 floats)
 };
 hipError_t launch_ffn_fwd_f32(const moe_shape_t& s, const ffn_args& a, hipStream_t st);

@@ -1,5 +1,5 @@
 // Greedy search for a lightweight expert placement (Section 4.3, Algorithm 1 of the paper) with its
-// performance model (Section 4.2, Eqs. 1-7; Section 5.3, Eq. 8), as one wavefront on the GPU: lane j
+// performance model (Section 4.2, Eqs. 1-6; Section 5.3, Eq. 8), as one wavefront on the GPU: lane j
 // is device j.  The search is a short serial loop over at most E selections; running it on the device
 // keeps the host out of the loop between the counts of one iteration and the dispatch of the next.
 // All decisions are integer except the comparison of two estimated times, which are IEEE doubles
@@ -32,7 +32,7 @@ __device__ __forceinline__ long long wave_sum_ll(long long v)
     return v;
 }
 
-// T'(R, H, s, n) from the largest R and H (Eq. 7, or Eq. 8 with overlap)
+// T'(R, H, s, n) from the largest R and H (Eq. 6, or Eq. 8 with overlap)
 __device__ __forceinline__ double layer_time(const moe_planner_t& c, long long max_r, long long max_h, int s, int n)
 {
     const double a2a = ((double)max_r * c.size_input) / c.B;                       // Eq. 1
@@ -40,7 +40,7 @@ __device__ __forceinline__ double layer_time(const moe_planner_t& c, long long m
     const double base = 4.0 * a2a + 3.0 * fec;
     const double tr = ((double)s * (double)(c.D - n) * c.size_params) / ((double)c.D * c.B);   // Eq. 4
     const double ag = ((double)s * (double)(c.D - n) * c.size_grads) / ((double)c.D * c.B);    // Eq. 5
-    if (!c.overlap) return (base + tr) + ag;                                       // Eq. 7
+    if (!c.overlap) return (base + tr) + ag;                                       // Eq. 6
     const double bec = 2.0 * fec;
     const double ptr = fmax(0.0, (tr - fec) - c.T_FNEC);                           // Eq. 8
     const double pag = fmax(0.0, (ag - bec) - c.T_BNEC);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(64) void plan_kernel(const moe_planner_t c, const i
     while (s < E) {
         const long long max_h = wave_max_ll(dev ? H : -1);
         const long long min_h = wave_min_ll(dev ? H : 0x7fffffffffffffffll);
-        if ((double)(max_h - min_h) < (c.alpha * (double)total) / (double)E) break;        // Eq. 9: balanced
+        if ((double)(max_h - min_h) < (c.alpha * (double)total) / (double)E) break;        // Eq. 7: balanced
         const int i = __ffsll((unsigned long long)__ballot(dev && H == max_h)) - 1;        // heaviest device, lowest index
         int best = -1;
         for (int e = i * epd; e < (i + 1) * epd; ++e)

@@ -316,8 +316,10 @@ hipError_t launch_dispatch_bwd(const moe_shape_t& s, const void* dXp, const int3
 // that will compute its inputs).  With every expert's parameters in one pool in this GPU's memory, the
 // transfer is a gather of the hosted experts into the group slots the grouped FFN reads, driven by the
 // plan as it lies in device memory: group g is the g-th expert e (ascending) with expert_dest[e] == self.
-// A slot that already holds the right expert is left alone (placements change little from one iteration to
-// the next, Section 3), which slot_expert[G] keeps track of.
+// A slot that already holds the right expert in its current version is left alone (placements change little
+// from one iteration to the next, Section 3), which slot_expert[G] and slot_version[G] keep track of: an
+// expert's parameters are updated before every transfer (Section 5.1), so the pool carries a version per
+// expert that the caller bumps with every update, and a replica of an older version is copied again.
 namespace {
 
 __device__ __forceinline__ int hosted_expert_of_group(const int32_t* __restrict__ expert_dest, int E, int self, int g)
@@ -334,12 +336,15 @@ __device__ __forceinline__ int hosted_expert_of_group(const int32_t* __restrict_
 }
 
 __global__ __launch_bounds__(256) void trans_gather_kernel(
-    const int32_t* __restrict__ expert_dest, const int32_t* __restrict__ slot_expert,
+    const int32_t* __restrict__ expert_dest, const int32_t* __restrict__ pool_version,
+    const int32_t* __restrict__ slot_expert, const int32_t* __restrict__ slot_version,
     const uint4* __restrict__ pool, uint4* __restrict__ groups, long vec_per_expert, int E, int self)
 {
     const int g = blockIdx.y;
     const int e = hosted_expert_of_group(expert_dest, E, self, g);
-    if (e < 0 || e == slot_expert[g]) return;              // unused slot, or the expert is already there
+    if (e < 0) return;                                     // unused slot
+    // the expert is already there, in the version the pool holds now (no versions given: always copied)
+    if (pool_version != nullptr && e == slot_expert[g] && slot_version[g] == pool_version[e]) return;
     const uint4* src = pool + (long)e * vec_per_expert;
     uint4* dst = groups + (long)g * vec_per_expert;
     const long stride = (long)gridDim.x * blockDim.x * 4;
@@ -358,28 +363,67 @@ __global__ __launch_bounds__(256) void trans_gather_kernel(
     }
 }
 
-__global__ void trans_commit_kernel(const int32_t* __restrict__ expert_dest, int32_t* __restrict__ slot_expert, int E, int self, int G)
+__global__ void trans_commit_kernel(const int32_t* __restrict__ expert_dest, const int32_t* __restrict__ pool_version,
+                                    int32_t* __restrict__ slot_expert, int32_t* __restrict__ slot_version, int E, int self, int G)
 {
     const int g = blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= G) return;
     const int e = hosted_expert_of_group(expert_dest, E, self, g);
-    if (e >= 0) slot_expert[g] = e;                        // an unused slot keeps what it holds
+    if (e >= 0) {                                          // an unused slot keeps what it holds
+        slot_expert[g] = e;
+        if (pool_version != nullptr) slot_version[g] = pool_version[e];
+    }
+}
+
+// Agg on one GPU (Section 4.1: the gradients a replica computed are added to the expert's gradient where its
+// parameters live).  The inverse walk of the gather above: the fp32 gradient of hosted group g is added to the
+// pool entry of the expert the plan puts there.  Every element is touched by one thread: same bits every run.
+__global__ __launch_bounds__(256) void agg_add_kernel(
+    const int32_t* __restrict__ expert_dest, const float4* __restrict__ groups, float4* __restrict__ pool,
+    long vec_per_expert, int E, int self)
+{
+    const int g = blockIdx.y;
+    const int e = hosted_expert_of_group(expert_dest, E, self, g);
+    if (e < 0) return;
+    const float4* src = groups + (long)g * vec_per_expert;
+    float4* dst = pool + (long)e * vec_per_expert;
+    const long stride = (long)gridDim.x * blockDim.x;
+    for (long v = (long)blockIdx.x * blockDim.x + threadIdx.x; v < vec_per_expert; v += stride) {
+        const float4 a = src[v];
+        float4 b = dst[v];
+        b.x += a.x; b.y += a.y; b.z += a.z; b.w += a.w;
+        dst[v] = b;
+    }
 }
 
 }  // namespace
 
-hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* slot_expert,
+hipError_t launch_agg_add(const moe_shape_t& s, const int32_t* expert_dest, const float* groups, float* pool,
+                          long floats_per_expert, hipStream_t st)
+{
+    const long vec = floats_per_expert / 4;
+    long bx = (vec + 256 * 4 - 1) / (256 * 4);
+    bx = bx < 1 ? 1 : (bx > 1024 ? 1024 : bx);
+    hipLaunchKernelGGL(agg_add_kernel, dim3((unsigned)bx, s.G), dim3(256), 0, st, expert_dest,
+                       (const float4*)groups, (float4*)pool, vec, s.E, s.self);
+    return hipGetLastError();
+}
+
+hipError_t launch_trans_gather(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* pool_version,
+                               const int32_t* slot_expert, const int32_t* slot_version,
                                const void* pool, void* groups, long bytes_per_expert, hipStream_t st)
 {
     const long vec = bytes_per_expert / 16;
     const int bx = (int)((vec + 256 * 4 - 1) / (256 * 4) < 512 ? (vec + 256 * 4 - 1) / (256 * 4) : 512);
-    hipLaunchKernelGGL(trans_gather_kernel, dim3(bx > 0 ? bx : 1, s.G), dim3(256), 0, st, expert_dest, slot_expert,
+    hipLaunchKernelGGL(trans_gather_kernel, dim3(bx > 0 ? bx : 1, s.G), dim3(256), 0, st, expert_dest, pool_version, slot_expert, slot_version,
                        (const uint4*)pool, (uint4*)groups, vec, s.E, s.self);
     return hipGetLastError();
 }
 
-hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, int32_t* slot_expert, hipStream_t st)
+hipError_t launch_trans_commit(const moe_shape_t& s, const int32_t* expert_dest, const int32_t* pool_version,
+                               int32_t* slot_expert, int32_t* slot_version, hipStream_t st)
 {
-    hipLaunchKernelGGL(trans_commit_kernel, dim3((s.G + 63) / 64), dim3(64), 0, st, expert_dest, slot_expert, s.E, s.self, s.G);
+    hipLaunchKernelGGL(trans_commit_kernel, dim3((s.G + 63) / 64), dim3(64), 0, st, expert_dest, pool_version, slot_expert,
+                       slot_version, s.E, s.self, s.G);
     return hipGetLastError();
 }

@@ -39,6 +39,77 @@ def rel_l2(got, want) -> float:
     return num / den if den > 0 else num
 
 
+def rows_close(got, want, tol: float, floor: float = 0.02, elt: float = 8.0):
+    """Row-by-row comparison of two arrays whose last axis is a row.  Returns (worst row error, its row,
+    worst element error in units of the row's rms, pooled rel-L2).  A row's error is ||got - want|| over
+    max(||want||, floor * typical row norm): the relative L2 error of that row, with rows far below the
+    typical norm measured against a floor so that an all-but-zero row does not divide by nothing."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    n = want.shape[-1] if want.ndim else 1
+    g2, w2 = got.reshape(-1, n), want.reshape(-1, n)
+    if w2.shape[0] == 0:
+        return 0.0, -1, 0.0, 0.0
+    rn = np.linalg.norm(w2, axis=1)
+    typical = float(np.sqrt(np.mean(rn * rn)))
+    den = np.maximum(rn, floor * typical)
+    diff = g2 - w2
+    if typical == 0.0:
+        worst = float(np.abs(diff).max())
+        return worst, int(np.argmax(np.abs(diff).max(axis=1))), worst, worst
+    err = np.linalg.norm(diff, axis=1) / den
+    r = int(np.argmax(err))
+    elt_err = float((np.abs(diff).max(axis=1) / (den / np.sqrt(n))).max())
+    return float(err[r]), r, elt_err, rel_l2(g2, w2)
+
+
+def assert_rows_close(got, want, tol: float, what: str = "", floor: float = 0.02, elt: float = 8.0, report=None):
+    """Every row within `tol` in relative L2, and every element within elt * tol of its row's rms: an error
+    confined to one row, one tile or a few elements fails even where the norm over the whole tensor would
+    hide it.  `report` (a list) collects (what, worst row error, pooled error) for printing."""
+    worst, r, elt_err, pooled = rows_close(got, want, tol, floor, elt)
+    if report is not None:
+        report.append((what, worst, pooled))
+    assert worst <= tol, f"{what}: row {r} off by {worst:.3e} (pooled {pooled:.3e}, tolerance {tol:g})"
+    assert elt_err <= elt * tol, f"{what}: an element off by {elt_err:.3e} of its row's rms (allowed {elt * tol:g})"
+    return worst
+
+
+# ---- which tiles the grouped matrix kernel works on (the test picks its samples from this; it mirrors the
+# kernel's tile walk: 256-row tiles from each group's first row, bands of 8 row tiles walked column by column,
+# and the tiles left after the last full round of the chip, which are split along the contraction)
+FFN_BM, FFN_BAND, FFN_SPLIT_UNITS = 256, 8, 320
+
+
+def ffn_row_tiles(group_rows):
+    """[(group, first row, end row)] of every 256-row tile, in the kernel's order."""
+    tiles = []
+    for g, (o, e) in enumerate(group_rows):
+        for r0 in range(o, e, FFN_BM):
+            tiles.append((g, r0, min(r0 + FFN_BM, e)))
+    return tiles
+
+
+def ffn_split_tiles(total_rt: int, col_tiles: int, k_slices: int, n_blocks: int):
+    """(row tile, column tile) of the tiles the last, contraction-split round covers; empty if there is none."""
+    n_act = total_rt * col_tiles
+    n_full = (n_act // n_blocks) * n_blocks
+    rem = n_act - n_full
+    if rem == 0 or k_slices < 128:
+        return []
+    S = min(4, n_blocks // rem, max(1, k_slices // 64))
+    if S <= 1 or rem * S > FFN_SPLIT_UNITS:
+        return []
+    out = []
+    for t in range(n_full, n_act):
+        band = t // (FFN_BAND * col_tiles)
+        in_band = t - band * FFN_BAND * col_tiles
+        band_rows = min(FFN_BAND, total_rt - band * FFN_BAND)
+        out.append((band * FFN_BAND + in_band % band_rows, in_band // band_rows))
+    return out
+
+
 def make_handle(cfg: wl.MoEConfig, G: Optional[int] = None) -> binding.Handle:
     return binding.Handle(T=cfg.T, d=cfg.d, h=cfg.h, E=cfg.E, k=cfg.k, P=cfg.P, self_dest=cfg.self_dest,
                           G=G if G is not None else cfg.G_max, dtype=cfg.dtype, act=cfg.act, renorm=cfg.renorm,
@@ -90,8 +161,9 @@ class Case:
             Yp[self.lay["pos"][self.hosted]] = self.oracle_ffn(self.hosted)
         return Yp
 
-    def sample_assignments(self, n_random: int, seed: int = 0) -> np.ndarray:
-        """Hosted assignments at group and tile boundaries plus random ones."""
+    def sample_assignments(self, n_random: int, seed: int = 0, every_tile: bool = False) -> np.ndarray:
+        """Hosted assignments at group and tile boundaries plus random ones; with `every_tile` also one row,
+        at a random place, in every 256-row tile of every hosted group (the last, ragged tile included)."""
         rng = np.random.default_rng(seed)
         rows = []
         for g in range(self.G):
@@ -99,6 +171,9 @@ class Case:
             for r in (o, o + 1, o + 255, o + 256, o + 257, e - 2, e - 1):
                 if o <= r < e:
                     rows.append(r)
+        if every_tile:
+            for _, r0, r1 in ffn_row_tiles([self.group_rows(g) for g in range(self.G)]):
+                rows.append(int(rng.integers(r0, r1)))
         perm = self.lay["perm"]
         a = [int(perm[r]) for r in rows]
         if self.hosted.size:

@@ -95,15 +95,28 @@ def test_trans_validates_arguments(lib):
     pools = (vp * 2)(0x1000, 0x2000)
     groups = (vp * 2)(0x3000, 0x4000)
     sizes = (ctypes.c_size_t * 2)(4096, 4096)
-    dest, slots = vp(0x5000), vp(0x6000)
-    assert lib.moe_trans(h, None, slots, 2, pools, groups, sizes, None) == -1
-    assert lib.moe_trans(h, dest, slots, 0, pools, groups, sizes, None) == -2
-    assert lib.moe_trans(h, dest, slots, 9, pools, groups, sizes, None) == -2
+    dest, slots, pver, sver = vp(0x5000), vp(0x6000), vp(0x7000), vp(0x8000)
+    assert lib.moe_trans(h, None, pver, slots, sver, 2, pools, groups, sizes, None) == -1
+    assert lib.moe_trans(h, dest, pver, slots, None, 2, pools, groups, sizes, None) == -1      # versions: both or neither
+    assert lib.moe_trans(h, dest, None, slots, sver, 2, pools, groups, sizes, None) == -1
+    assert lib.moe_trans(h, dest, pver, slots, sver, 0, pools, groups, sizes, None) == -2
+    assert lib.moe_trans(h, dest, pver, slots, sver, 9, pools, groups, sizes, None) == -2
     bad_sizes = (ctypes.c_size_t * 2)(4096, 4100)                   # not a multiple of 16
-    assert lib.moe_trans(h, dest, slots, 2, pools, groups, bad_sizes, None) == -2
+    assert lib.moe_trans(h, dest, pver, slots, sver, 2, pools, groups, bad_sizes, None) == -2
     bad_pools = (vp * 2)(0x1000, 0x2004)                            # misaligned
-    assert lib.moe_trans(h, dest, slots, 2, bad_pools, groups, sizes, None) == -2
+    assert lib.moe_trans(h, dest, None, slots, None, 2, bad_pools, groups, sizes, None) == -2
     missing = (vp * 2)(0x1000, 0)
-    assert lib.moe_trans(h, dest, slots, 2, missing, groups, sizes, None) == -1
+    assert lib.moe_trans(h, dest, pver, slots, sver, 2, missing, groups, sizes, None) == -1
     assert lib.moe_destroy(h) == 0
 
+
+def test_settings_validate_arguments(lib):
+    """moe_set_act_saved takes 0 or 1."""
+    from paper_2411_10003_amd.binding import _Shape
+    vp = ctypes.c_void_p
+    big = _Shape(1 << 22, 64, 128, 1024, 1, 4, 0, 2, 1, 0, 0)       # 16384 chunks x 1024 experts = 2^24 words
+    h = ctypes.c_void_p()
+    assert lib.moe_create(ctypes.byref(h), ctypes.byref(big)) == 0
+    assert lib.moe_set_act_saved(h, 2) == -2 and lib.moe_set_act_saved(h, 1) == 0 and lib.moe_set_act_saved(h, 0) == 0
+    assert lib.moe_set_act_saved(None, 1) == -1
+    assert lib.moe_destroy(h) == 0

@@ -37,5 +37,38 @@ def test_result_line_has_the_contract_keys():
     rf = res["roofline"]
     assert set(("bound", "achieved", "peak", "unit", "frac", "traffic")) <= set(rf)
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9
+    assert {"measured_peak", "frac_of_measured", "per_group", "median_ms_per_step", "min_ms_per_step"} <= set(rf)
+    assert rf["measured_peak"]["mfma_TFLOP/s"] > 100 and rf["measured_peak"]["copy_GB/s"] > 500
+    gate = res["per_call"]["gate_topk"]
+    assert {"ms", "median_ms", "min_ms", "hbm_frac", "matrix_frac", "bound"} <= set(gate)
     cb = res["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
+
+
+def test_traffic_comes_from_the_counter_summary_and_names_its_workload():
+    """roofline.traffic is parsed from the committed counter summary; a summary of another workload is refused."""
+    sys.path.insert(0, ROOT)
+    import bench
+    path = bench.TRAFFIC_PROFILES[3]
+    text = open(path).read()
+    import re
+    flops = float(re.search(r"algorithmic flops per step ([0-9.eE+]+)", text).group(1))
+    t = bench.measured_traffic(3, flops)
+    assert t is not None and 1e10 < t < 1e12
+    assert bench.measured_traffic(1, 1.0) is None                    # no summary for that configuration
+    with pytest.raises(SystemExit):
+        bench.measured_traffic(3, flops * 1.1)
+
+
+def test_group_bounds_follow_the_rooflines():
+    """A group of few rows is bound by its weight bytes, a large one by the matrix cores; an empty one still pays
+    for writing its gradients."""
+    sys.path.insert(0, ROOT)
+    import bench
+    from paper_2411_10003_amd import workload as wl
+    cfg = wl.CONFIGS[4]
+    gb = bench.ffn_group_bounds(cfg, [0, 40, 12000], True)
+    assert [g["bound"] for g in gb] == ["hbm", "hbm", "mfma"]
+    w_bytes = 2 * cfg.d * cfg.h * 2
+    assert abs(gb[0]["bound_us"] - (2 * w_bytes + 2 * cfg.d * cfg.h * 4) / 8e12 * 1e6) < 0.1
+    assert abs(gb[2]["bound_us"] - 3 * 2.0 * 12000 * cfg.d * cfg.h * 2 / 2.5e15 * 1e6) < 0.1

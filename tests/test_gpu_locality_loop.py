@@ -1,9 +1,13 @@
-"""The locality loop on one GPU (Sections 3 and 5.1 of the paper): the plan of iteration i+1 is searched on
+"""The locality loop on one GPU (Sections 3, 4.1 and 5.1 of the paper): the plan of iteration i+1 is searched on
 the device from the counts of iteration i, on a second stream while iteration i computes; the hosted experts'
-parameters follow the plan through moe_trans; the host never reads counts or plans inside the loop.
+parameters follow the plan through moe_trans, which copies a replica again when the expert's parameters have
+been updated since (an optimizer step between iterations changes some experts and bumps their versions); every
+iteration runs forward and backward, and the weight gradients of the hosted groups are added per expert through
+moe_agg while the plan, and with it the meaning of a group slot, changes.  The host never reads counts or plans
+inside the loop.
 
-Every iteration's layout, parameter slots and layer output are compared with the oracle, which plans with the
-planner oracle from the same count matrices.
+Every iteration's layout, parameter slots and layer output, and the per-expert gradients accumulated over the
+whole sweep, are compared with the oracle, which plans with the planner oracle from the same count matrices.
 """
 import numpy as np
 import pytest
@@ -33,6 +37,12 @@ def test_drift_sweep_with_device_side_planning():
     W1g = torch.zeros(G_cap, d, h, dtype=torch.bfloat16, device=G.DEV)
     W2g = torch.zeros(G_cap, h, d, dtype=torch.bfloat16, device=G.DEV)
     slot_expert = torch.full((G_cap,), -1, dtype=torch.int32, device=G.DEV)
+    slot_version = torch.full((G_cap,), -1, dtype=torch.int32, device=G.DEV)
+    pool_version = torch.zeros(E, dtype=torch.int32, device=G.DEV)
+    gW1_all = torch.zeros(E, d, h, dtype=torch.float32, device=G.DEV)       # per-expert gradient pools (Agg)
+    gW2_all = torch.zeros(E, h, d, dtype=torch.float32, device=G.DEV)
+    # the optimizer step between iterations i-1 and i: the experts e = i mod 3 (mod 3) change sign (exact in bf16)
+    updated = [np.arange(E)[np.arange(E) % 3 == i % 3] if i > 0 else np.zeros(0, np.int64) for i in range(iters)]
 
     # ---- oracle pass over the sweep: routing, count matrices, plans
     inputs = [wl.make_inputs(cfg, i, with_weights=False) for i in range(iters)]
@@ -47,7 +57,7 @@ def test_drift_sweep_with_device_side_planning():
 
     # ---- device pass.  The other devices' count rows are uploaded once; row `self` is filled from device counts.
     hd = G.make_handle(cfg, G=G_cap)
-    b = binding.LayerBuffers(hd, False)
+    b = binding.LayerBuffers(hd, True)
     gat_dev = []
     for g in gatings:
         gg = g.copy(); gg[me] = -7                                 # poison: must be overwritten on the device
@@ -68,8 +78,14 @@ def test_drift_sweep_with_device_side_planning():
         else:
             main.wait_stream(side)                                 # the plan searched during the previous iteration
         plan_row = cur.expert_dest[me]
-        hd.trans(plan_row, slot_expert, [dW1_all, dW2_all], [W1g, W2g])
-        hd.dispatch(plan_row, dX, b.idx, b.counts, b.layout, b.Xp)
+        if updated[i].size:                                        # parameters of some experts were updated
+            ue = torch.from_numpy(updated[i]).to(G.DEV)
+            dW1_all[ue] = -dW1_all[ue]
+            dW2_all[ue] = -dW2_all[ue]
+            pool_version[ue] += 1
+        hd.trans(plan_row, slot_expert, [dW1_all, dW2_all], [W1g, W2g], pool_version, slot_version)
+        # the per-chunk histograms of moe_expert_counts are still in the workspace: nothing has used it since
+        hd.dispatch_after_counts(plan_row, dX, b.idx, b.counts, b.layout, b.Xp)
         counts_ready.record(main)
         if i + 1 < iters:                                          # plan of iteration i+1 beside the expert computation
             side.wait_event(counts_ready)
@@ -83,34 +99,67 @@ def test_drift_sweep_with_device_side_planning():
         b.Yp.copy_(G.dev(x["Yp_fill"], "bf16"))
         hd.expert_ffn_fwd(b.Xp, b.layout, W1g, W2g, None, b.Yp, b.Z, b.U)
         hd.combine(b.Yp, b.layout.pos, b.w, b.out)
+        b.dXp.copy_(G.dev(x["dXp_fill"], "bf16"))
+        hd.combine_bwd(G.dev(x["dOut"], "bf16"), b.Yp, b.layout.pos, b.w, b.dYp, b.dw)
+        hd.expert_ffn_bwd(b.dYp, b.Xp, b.Z, b.U, b.layout, W1g, W2g, None, b.dXp, b.dW1, b.dW2, None)
+        hd.agg(plan_row, [b.dW1, b.dW2], [gW1_all, gW2_all])       # slot gradients -> per-expert gradients
         main.wait_stream(side)                                     # b.counts is overwritten by the next iteration
         torch.cuda.synchronize()
         assert hd.read_status() == 0
         results.append(dict(plan=G.host(plan_row).copy(), slots=G.host(slot_expert).copy(), out=G.host(b.out).copy(),
                             lay={n: G.host(getattr(b.layout, n)).copy() for n in
                                  ("slot_of_expert", "slot_offsets", "dest_offsets", "dest_slots", "pos", "perm")},
-                            W1g=G.host(W1g).copy(), counts=G.host(b.counts).copy()))
+                            W1g=G.host(W1g).copy(), W2g=G.host(W2g).copy(), counts=G.host(b.counts).copy(),
+                            versions=G.host(slot_version).copy()))
 
     # ---- comparison, iteration by iteration
     held = np.full(G_cap, -1, dtype=np.int64)
+    held_ver = np.full(G_cap, -1, dtype=np.int64)
+    ver = np.zeros(E, dtype=np.int64)
+    gW1_ref, gW2_ref = np.zeros((E, d, h)), np.zeros((E, h, d))
+    ever_hosted = np.zeros(E, dtype=bool)
+    recopied = 0
     for i in range(iters):
         r, res, dest = routes[i], results[i], dest_of_iter[i]
+        W1_all[updated[i]] *= -1.0                                 # the same optimizer step on the host
+        W2_all[updated[i]] *= -1.0
+        ver[updated[i]] += 1
         assert np.array_equal(res["counts"], r["counts"])
         assert np.array_equal(res["plan"], dest), f"iteration {i}: plan"
         lay = G.orc.place(r["idx"], r["counts"], dest, P)
         for n in lay:
             assert np.array_equal(res["lay"][n], lay[n]), (i, n)
         hosted_e = wl.hosted_experts(dest, me)
+        recopied += int(((held[:hosted_e.size] == hosted_e) & (held_ver[:hosted_e.size] != ver[hosted_e])).sum())
         held[:hosted_e.size] = hosted_e                            # slots beyond the hosted experts keep what they had
+        held_ver[:hosted_e.size] = ver[hosted_e]
         assert np.array_equal(res["slots"], held), f"iteration {i}: slot bookkeeping"
+        assert np.array_equal(res["versions"], held_ver), f"iteration {i}: version bookkeeping"
+        # the slots hold the parameters as they are NOW, also where the expert stayed and only its values changed
         assert np.array_equal(res["W1g"][:hosted_e.size], W1_all[hosted_e]), f"iteration {i}: parameters in the slots"
+        assert np.array_equal(res["W2g"][:hosted_e.size], W2_all[hosted_e]), f"iteration {i}: parameters in the slots"
         goe = wl.group_of_expert(dest, me)
         idx_flat = r["idx"].reshape(-1)
         hosted_a = G.orc.hosted_assignments(idx_flat, goe)
         Yp = inputs[i]["Yp_fill"].astype(np.float64)
+        W1o = np.zeros((G_cap, d, h), np.float32); W2o = np.zeros((G_cap, h, d), np.float32)
+        W1o[:hosted_e.size] = W1_all[hosted_e]; W2o[:hosted_e.size] = W2_all[hosted_e]
         if hosted_a.size:
-            W1o = np.zeros((G_cap, d, h), np.float32); W2o = np.zeros((G_cap, h, d), np.float32)
-            W1o[:hosted_e.size] = W1_all[hosted_e]; W2o[:hosted_e.size] = W2_all[hosted_e]
             Yp[lay["pos"][hosted_a]] = G.orc.ffn_fwd(inputs[i]["X"], idx_flat, goe, W1o, W2o, None, k, cfg.act, hosted_a)
         want = G.orc.combine(Yp, lay["pos"], r["w"], k)
-        assert G.rel_l2(res["out"], want) <= G.TOL["bf16"], f"iteration {i}: layer output"
+        G.assert_rows_close(res["out"], want, G.TOL["bf16"], f"iteration {i}: layer output")
+        # backward of the same iteration: the hosted groups' weight gradients, added to their experts
+        dYp_o, _ = G.orc.combine_bwd(inputs[i]["dOut"], Yp, lay["pos"], r["w"], k)
+        g1, g2, _ = G.orc.ffn_bwd_weights(inputs[i]["X"], idx_flat, goe, W1o, W2o, None, k, cfg.act,
+                                          dYp_o[lay["pos"]].astype(np.float32), G_cap)
+        gW1_ref[hosted_e] += g1[:hosted_e.size]
+        gW2_ref[hosted_e] += g2[:hosted_e.size]
+        ever_hosted[hosted_e] = True
+    assert recopied > 0, "the sweep should contain a replica that stayed in its slot while its parameters changed"
+    got1, got2 = G.host(gW1_all), G.host(gW2_all)
+    assert not got1[~ever_hosted].any() and not got2[~ever_hosted].any()       # experts never hosted: untouched
+    with_rows = [e for e in np.nonzero(ever_hosted)[0] if gW1_ref[e].any()]
+    assert len(with_rows) > E // P, "gradients should reach replicated experts too"
+    for e in np.nonzero(ever_hosted)[0]:
+        G.assert_rows_close(got1[e], gW1_ref[e], G.TOL["bf16"], f"accumulated dW1 of expert {e}")
+        G.assert_rows_close(got2[e], gW2_ref[e], G.TOL["bf16"], f"accumulated dW2 of expert {e}")

@@ -163,6 +163,45 @@ def test_dispatch_with_empty_experts_and_one_giant_group(G, orc):
     assert np.array_equal(G.host(b.Xp), orc.dispatch(case.inp["X"], lay["perm"], cfg.k))
 
 
+def test_dispatch_depends_on_its_arguments_only(G, orc):
+    """moe_dispatch keeps nothing from earlier calls: rewriting idx in place after moe_expert_counts, or another
+    handle counting into the same workspace in between, must not change its result.  moe_dispatch_after_counts is
+    the explicit form for the unbroken sequence counts -> dispatch and gives the same bits."""
+    cfg = _cfg(1, T=1500, d=128, h=64)
+    case = G.Case(cfg)
+    hd = G.make_handle(cfg)
+    b = G.binding.LayerBuffers(hd, False)
+    idx1 = case.route["idx"]
+    rng = np.random.default_rng(5)
+    idx2 = np.stack([rng.permutation(cfg.E)[:cfg.k] for _ in range(cfg.T)]).astype(np.int32)   # another routing
+    cnt2 = orc.counts(idx2, cfg.E)
+    lay2 = orc.place(idx2, cnt2, case.expert_dest, cfg.P)
+    # (a) idx rewritten in place between the two calls
+    d_idx = G.dev(idx1)
+    hd.expert_counts(d_idx, b.counts)
+    d_idx.copy_(G.dev(idx2))
+    hd.dispatch(case.ddest, case.dX, d_idx, G.dev(cnt2), b.layout, b.Xp)
+    torch.cuda.synchronize()
+    G.assert_layout_equal(b, lay2)
+    assert np.array_equal(G.host(b.Xp), orc.dispatch(case.inp["X"], lay2["perm"], cfg.k))
+    # (b) a second handle used the same workspace in between
+    hd_other = G.make_handle(cfg)
+    hd_other.ws = hd.ws
+    d_idx1, d_idx2 = G.dev(idx1), G.dev(idx2)
+    hd.expert_counts(d_idx1, b.counts)
+    hd_other.expert_counts(d_idx2, torch.empty_like(b.counts))
+    hd.dispatch(case.ddest, case.dX, d_idx1, b.counts, b.layout, b.Xp)
+    torch.cuda.synchronize()
+    G.assert_layout_equal(b, case.lay)
+    # (c) the explicit reuse after an unbroken counts call
+    b3 = G.binding.LayerBuffers(hd, False)
+    hd.expert_counts(d_idx1, b3.counts)
+    hd.dispatch_after_counts(case.ddest, case.dX, d_idx1, b3.counts, b3.layout, b3.Xp)
+    torch.cuda.synchronize()
+    G.assert_layout_equal(b3, case.lay)
+    assert torch.equal(b3.Xp, b.Xp) and np.array_equal(G.host(b3.Xp), orc.dispatch(case.inp["X"], case.lay["perm"], cfg.k))
+
+
 def test_plan_errors_are_reported(G):
     cfg = _cfg(1, T=128, d=64, h=64)
     case = G.Case(cfg)
@@ -213,10 +252,10 @@ def test_ffn_forward_and_combine(G, orc, cfg):
     Y, Z, U, Act = case.oracle_ffn(hosted, True)
     rows = pos[hosted]
     Yp_gpu = G.host(b.Yp)
-    assert G.rel_l2(Yp_gpu[rows], Y) <= tol
-    assert G.rel_l2(G.host(b.Z)[rows], Z) <= tol
+    G.assert_rows_close(Yp_gpu[rows], Y, tol, "Yp_gpu[rows]")
+    G.assert_rows_close(G.host(b.Z)[rows], Z, tol, "b.Z[rows]")
     if cfg.act == "swiglu":
-        assert G.rel_l2(G.host(b.U)[rows], U) <= tol
+        G.assert_rows_close(G.host(b.U)[rows], U, tol, "b.U[rows]")
     # rows of other destinations are untouched
     remote = np.setdiff1d(np.arange(cfg.A), rows)
     assert np.array_equal(Yp_gpu[remote], case.inp["Yp_fill"][remote])
@@ -228,7 +267,7 @@ def test_ffn_forward_and_combine(G, orc, cfg):
     hd.combine(G.dev(Yp_in, cfg.dtype), G.dev(pos), G.dev(w32), b.out)
     torch.cuda.synchronize()
     want = orc.combine(Yp_in, pos, w32, cfg.k)
-    assert G.rel_l2(G.host(b.out), want) <= tol
+    G.assert_rows_close(G.host(b.out), want, tol, "b.out")
     # end to end (device routing and device FFN output) against the oracle chain
     G.gpu_route(hd, case, b)
     hd.dispatch(case.ddest, case.dX, b.idx, b.counts, b.layout, b.Xp)
@@ -236,7 +275,7 @@ def test_ffn_forward_and_combine(G, orc, cfg):
     hd.combine(b.Yp, b.layout.pos, b.w, b.out)
     torch.cuda.synchronize()
     want = orc.combine(case.oracle_Yp_full(), pos, case.route["w"], cfg.k)
-    assert G.rel_l2(G.host(b.out), want) <= tol
+    G.assert_rows_close(G.host(b.out), want, tol, "b.out")
 
 
 def test_identity_experts_return_x_times_weight_sum(G):
@@ -249,7 +288,7 @@ def test_identity_experts_return_x_times_weight_sum(G):
     hd.combine(b.Xp, b.layout.pos, b.w, b.out)                   # Yp := Xp on all rows
     torch.cuda.synchronize()
     want = case.inp["X"].astype(np.float64) * case.route["w"].sum(axis=1, keepdims=True)
-    assert G.rel_l2(G.host(b.out), want) <= 4e-3                 # one bf16 rounding of the output
+    G.assert_rows_close(G.host(b.out), want, 4e-3, "b.out")   # one bf16 rounding of the output
 
 
 @pytest.mark.parametrize("cfg", [c for c in FFN_CASES if c.backward],
@@ -272,8 +311,8 @@ def test_backward_calls(G, orc, cfg):
     hd.combine_bwd(G.dev(inp["dOut"], dt), G.dev(Yp_in, dt), G.dev(pos), G.dev(w32), b.dYp, b.dw)
     torch.cuda.synchronize()
     dYp_o, dw_o = orc.combine_bwd(inp["dOut"], Yp_in, pos, w32, cfg.k)
-    assert G.rel_l2(G.host(b.dYp), dYp_o) <= tol
-    assert G.rel_l2(G.host(b.dw), dw_o) <= tol
+    G.assert_rows_close(G.host(b.dYp), dYp_o, tol, "b.dYp")
+    G.assert_rows_close(G.host(b.dw), dw_o, tol, "b.dw", floor=1.0)
 
     # --- expert_ffn_bwd on shared inputs: dYp = oracle's, rounded to the storage type
     dYp_in = dYp_o.astype(np.float32)
@@ -286,21 +325,46 @@ def test_backward_calls(G, orc, cfg):
     dXh = orc.ffn_bwd_rows(inp["X"], case.idx_flat, case.goe, inp["W1"], inp["W2"], inp.get("W3"), cfg.k, cfg.act,
                            hosted, dYp_in[pos[hosted]].astype(np.float64))
     dXp_gpu = G.host(b.dXp)
-    assert G.rel_l2(dXp_gpu[pos[hosted]], dXh) <= tol
+    G.assert_rows_close(dXp_gpu[pos[hosted]], dXh, tol, "dXp_gpu[pos[hosted]]")
     remote = np.setdiff1d(np.arange(cfg.A), pos[hosted])
     assert np.array_equal(dXp_gpu[remote], inp["dXp_fill"][remote])
     dYa = dYp_in[pos]                                            # by assignment
     dW1o, dW2o, dW3o = orc.ffn_bwd_weights(inp["X"], case.idx_flat, case.goe, inp["W1"], inp["W2"], inp.get("W3"),
                                            cfg.k, cfg.act, dYa, cfg.G_max)
     Gn = case.G
-    assert G.rel_l2(G.host(b.dW1)[:Gn], dW1o[:Gn]) <= tol
-    assert G.rel_l2(G.host(b.dW2)[:Gn], dW2o[:Gn]) <= tol
+    G.assert_rows_close(G.host(b.dW1)[:Gn], dW1o[:Gn], tol, "b.dW1[:Gn]")
+    G.assert_rows_close(G.host(b.dW2)[:Gn], dW2o[:Gn], tol, "b.dW2[:Gn]")
     if cfg.act == "swiglu":
-        assert G.rel_l2(G.host(b.dW3)[:Gn], dW3o[:Gn]) <= tol
+        G.assert_rows_close(G.host(b.dW3)[:Gn], dW3o[:Gn], tol, "b.dW3[:Gn]")
     for g in range(cfg.G_max):                                   # empty or unused groups are written as zeros
         o, e = case.group_rows(g) if g < Gn else (0, 0)
         if e == o:
             assert not G.host(b.dW1)[g].any() and not G.host(b.dW2)[g].any()
+
+    # --- the activation of the forward pass read from the workspace instead of being recomputed (moe_set_act_saved):
+    # the forward call puts it back there; what does not depend on it keeps its bits, dW2 stays within tolerance
+    if dt == "bf16":
+        plain = [t.clone() if t is not None else None for t in (b.dW1, b.dW2, b.dW3, b.dXp)]
+        hd.expert_ffn_fwd(b.Xp, b.layout, case.dW1, case.dW2, case.dW3, b.Yp, b.Z, b.U)
+        hd.set_act_saved(True)
+        b.dW2.fill_(float("nan"))
+        hd.expert_ffn_bwd(G.dev(dYp_in, dt), b.Xp, b.Z, b.U, b.layout, case.dW1, case.dW2, case.dW3,
+                          b.dXp, b.dW1, b.dW2, b.dW3)
+        hd.set_act_saved(False)
+        torch.cuda.synchronize()
+        assert torch.equal(b.dW1, plain[0]) and torch.equal(b.dXp, plain[3])
+        if cfg.act == "swiglu":
+            assert torch.equal(b.dW3, plain[2])
+        G.assert_rows_close(G.host(b.dW2)[:Gn], dW2o[:Gn], tol, "dW2 from the saved activation")
+        for g in range(cfg.G_max):
+            o, e = case.group_rows(g) if g < Gn else (0, 0)
+            if e == o:
+                assert not G.host(b.dW2)[g].any()
+        # back to the recomputed form for what follows
+        hd.expert_ffn_bwd(G.dev(dYp_in, dt), b.Xp, b.Z, b.U, b.layout, case.dW1, case.dW2, case.dW3,
+                          b.dXp, b.dW1, b.dW2, b.dW3)
+        torch.cuda.synchronize()
+        assert torch.equal(b.dW2, plain[1])
 
     # --- accumulate form: a second contribution is added to what the buffers hold.  Doubling is exact in
     # fp32, so running the same backward again on top must give exactly twice the first result; seeding the
@@ -320,8 +384,8 @@ def test_backward_calls(G, orc, cfg):
     hd.expert_ffn_bwd_acc(G.dev(dYp_in, dt), b.Xp, b.Z, b.U, b.layout, case.dW1, case.dW2, case.dW3,
                           b.dXp, b.dW1, b.dW2, b.dW3)
     torch.cuda.synchronize()
-    assert G.rel_l2(G.host(b.dW1)[:Gn] - 0.5, dW1o[:Gn]) <= tol
-    assert G.rel_l2(G.host(b.dW2)[:Gn] + 0.25, dW2o[:Gn]) <= tol
+    G.assert_rows_close(G.host(b.dW1)[:Gn] - 0.5, dW1o[:Gn], tol, "b.dW1[:Gn] - 0.5")
+    G.assert_rows_close(G.host(b.dW2)[:Gn] + 0.25, dW2o[:Gn], tol, "b.dW2[:Gn]  0.25")
     for g in range(cfg.G_max):                                   # an empty or unused group adds zero
         o, e = case.group_rows(g) if g < Gn else (0, 0)
         if e == o:
@@ -333,8 +397,10 @@ def test_backward_calls(G, orc, cfg):
     dw32 = dw_o.astype(np.float32)
     hd.gate_bwd(G.dev(dw32), G.dev(r["logits"]), G.dev(r["idx"]), b.dlogits)
     torch.cuda.synchronize()
-    assert G.rel_l2(G.host(b.dX), orc.dispatch_bwd(dXp_in, pos, cfg.k)) <= tol
-    assert G.rel_l2(G.host(b.dlogits), orc.gate_bwd(dw32, r["logits"], r["idx"], cfg.renorm)) <= 1e-5
+    G.assert_rows_close(G.host(b.dX), orc.dispatch_bwd(dXp_in, pos, cfg.k), tol, "b.dX")
+    # a token's logit gradient is a difference of nearly equal terms where its two gate weights or their gradients
+    # are close: measured against the typical row, not against what is left after the cancellation
+    G.assert_rows_close(G.host(b.dlogits), orc.gate_bwd(dw32, r["logits"], r["idx"], cfg.renorm), 1e-5, "b.dlogits", floor=1.0)
 
 
 @pytest.mark.parametrize("cfg", [c for c in FFN_CASES if c.backward][:3],
@@ -361,16 +427,19 @@ def test_layer_forward_backward_end_to_end(G, orc, cfg):
     dW1o, dW2o, dW3o = orc.ffn_bwd_weights(inp["X"], case.idx_flat, case.goe, inp["W1"], inp["W2"], inp.get("W3"),
                                            cfg.k, cfg.act, dYp_o[pos].astype(np.float32), cfg.G_max)
     Gn = case.G
-    assert G.rel_l2(G.host(b.out), orc.combine(Yp_o, pos, r["w"], cfg.k)) <= tol
-    assert G.rel_l2(G.host(b.dw), dw_o) <= tol
-    assert G.rel_l2(G.host(b.dX), orc.dispatch_bwd(dXp_o, pos, cfg.k)) <= tol
-    assert G.rel_l2(G.host(b.dW1)[:Gn], dW1o[:Gn]) <= tol
-    assert G.rel_l2(G.host(b.dW2)[:Gn], dW2o[:Gn]) <= tol
+    G.assert_rows_close(G.host(b.out), orc.combine(Yp_o, pos, r["w"], cfg.k), tol, "b.out")
+    G.assert_rows_close(G.host(b.dw), dw_o, tol, "b.dw", floor=1.0)
+    G.assert_rows_close(G.host(b.dX), orc.dispatch_bwd(dXp_o, pos, cfg.k), tol, "b.dX")
+    G.assert_rows_close(G.host(b.dW1)[:Gn], dW1o[:Gn], tol, "b.dW1[:Gn]")
+    G.assert_rows_close(G.host(b.dW2)[:Gn], dW2o[:Gn], tol, "b.dW2[:Gn]")
     if cfg.act == "swiglu":
-        assert G.rel_l2(G.host(b.dW3)[:Gn], dW3o[:Gn]) <= tol
-    # d_gate: compared against the norm of the gate-weight gradient it is a linear image of
+        G.assert_rows_close(G.host(b.dW3)[:Gn], dW3o[:Gn], tol, "b.dW3[:Gn]")
+    # d_gate, the plain relative L2 error over the whole tensor (observed about 2e-3)
     dl_o = orc.gate_bwd(dw_o, r["logits"], r["idx"], cfg.renorm)
-    assert np.linalg.norm(G.host(b.dlogits) - dl_o) <= tol * max(np.linalg.norm(dw_o), np.linalg.norm(dl_o))
+    dl_err = float(np.linalg.norm(G.host(b.dlogits) - dl_o))
+    print(f"[{cfg.dtype}-{cfg.act}-T{cfg.T}] end-to-end dlogits: plain rel-L2 {dl_err / np.linalg.norm(dl_o):.3e}, "
+          f"against max(|dw|, |dlogits|) {dl_err / max(np.linalg.norm(dw_o), np.linalg.norm(dl_o)):.3e}", flush=True)
+    assert dl_err <= tol * np.linalg.norm(dl_o)                # the plain relative L2 error
 
 
 def test_argument_errors_do_not_launch(G):

@@ -53,7 +53,7 @@ GATING4 = np.array([[6, 1, 1, 0], [5, 2, 0, 1], [4, 0, 3, 1], [1, 1, 0, 6]], dty
 
 
 def test_hand_traced_example():
-    """The example traced by hand in the oracle's pins (Algorithm 1, Eq. 7 and Eq. 8)."""
+    """The example traced by hand in the oracle's pins (Algorithm 1, Eq. 6 and Eq. 8)."""
     out, r = check(GATING4, 1, model())
     assert G.host(out.selected)[:4].tolist() == [0, 1, 3, 2] and int(G.host(out.info)[0]) == 1
     assert G.host(out.times)[:6].tolist() == [88.0, 38.0, 38.0, 41.0, 40.0, 43.0]
@@ -86,9 +86,27 @@ def test_config_shaped_count_matrices(index, overlap):
     case = G.Case(small)
     g = wl.make_gating(small, case.route["counts"]).astype(np.int64)
     consts = wl.planner_constants(cfg)
+    H0, R0 = po.loads(g, po.placement(cfg.P, cfg.E, [], []))
     for n in sorted({0, 1, cfg.P // 2, cfg.P - 1}):
-        out, r = check(g, n, po.PlannerModel(alpha=1.0, overlap=overlap, **consts))
-        assert r["T_output"] <= r["T_base"]
+        m = po.PlannerModel(alpha=1.0, overlap=overlap, **consts)
+        out, r = check(g, n, m)
+        times, H_dev = G.host(out.times), G.host(out.H)
+        assert times[1] <= times[0]                            # the device's plan is never worse than no placement
+        assert int(H_dev.sum()) == int(g.sum())
+        # the ablation's fixed policies (Section 6.4: the r heaviest experts go to every device) through the same
+        # performance model, and the balance degree (Section 6.3) before and after
+        line = [f"none T'={times[0]:.4g} RB={po.balance_degree(H0):.0f}",
+                f"greedy(n={n}) T'={times[1]:.4g} RB={po.balance_degree(H_dev):.0f} kept={int(G.host(out.info)[0])}"]
+        for r_top in (2, 3):
+            Ht, Rt = po.loads(g, po.top_policy(g, r_top))
+            T_top = po.layer_time(Rt, Ht, r_top, 0, m)
+            line.append(f"top{r_top} T'={T_top:.4g} RB={po.balance_degree(Ht):.0f}")
+            # with n = 0 a selected expert goes to every device, as under the fixed policies: whenever the search's
+            # first r selections are the r heaviest experts it has evaluated exactly that placement
+            order = sorted(range(cfg.E), key=lambda e: (-int(g[:, e].sum()), e))[:r_top]
+            if n == 0 and sorted(r["L"][:r_top]) == sorted(order) and len(r["L"]) >= r_top:
+                assert times[1] <= T_top
+        print(f"[cfg{index} overlap={overlap}] " + "; ".join(line), flush=True)
 
 
 def test_degenerate_inputs():
