@@ -47,7 +47,8 @@ typedef enum {
     MOE_ERR_WORKSPACE = -4,     /* workspace missing or misaligned */
     MOE_ERR_DTYPE = -5,
     MOE_ERR_UNIMPLEMENTED = -6,
-    MOE_ERR_HIP = -7            /* a HIP call failed; see moe_last_hip_error() */
+    MOE_ERR_HIP = -7,           /* a HIP call failed; see moe_last_hip_error() */
+    MOE_ERR_TOO_LARGE = -8      /* moe_expert_counts_static: the input needs more than the built-in scratch array */
 } moe_status_t;
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
@@ -120,6 +121,16 @@ int moe_gate_topk(moe_handle_t h, const void* X, const float* Wg, const float* b
 /* Input distribution (Section 3: the number of inputs each expert processes; what the planner's
  * search consumes).  in: idx[A]; out: counts[E].  Uses the workspace. */
 int moe_expert_counts(moe_handle_t h, const int32_t* idx, int32_t* counts, void* ws, void* stream);
+
+/* moe_expert_counts for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same output, same kernels; the
+ * per-chunk histograms live in an array built into the library (4 MiB of device memory per GPU the library
+ * runs on, held until the process ends) instead of the workspace.  The call allocates and frees nothing.
+ *   limit: ceil(T*k / 256) * E <= 2^20 words, else MOE_ERR_TOO_LARGE and nothing is enqueued
+ *   Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ *   threads) race.  The array keeps the last call's contents; every word a call reads it has written first,
+ *   so nothing needs clearing between calls. */
+int moe_expert_counts_static(moe_handle_t h, const int32_t* idx, int32_t* counts, void* stream);
 
 /* Placement-aware send buffer (Section 4.1: inputs of an expert whose parameters are on this
  * device are computed locally, the others go to the expert's owner; Fig. 2: first all-to-all).

@@ -25,7 +25,7 @@ EXPORTS = [
     "moe_read_status", "moe_gate_topk", "moe_expert_counts", "moe_dispatch", "moe_expert_ffn_fwd",
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
     "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans", "moe_recv_layout",
-    "moe_dispatch_after_counts", "moe_set_act_saved", "moe_agg", "moe_calib_copy", "moe_calib_mfma",
+    "moe_dispatch_after_counts", "moe_set_act_saved", "moe_expert_counts_static", "moe_agg", "moe_calib_copy", "moe_calib_mfma",
 ]
 
 
@@ -75,6 +75,7 @@ def load() -> ctypes.CDLL:
         lib.moe_dispatch.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(_Layout), vp, vp, vp]
         lib.moe_dispatch_after_counts.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(_Layout), vp, vp, vp]
         lib.moe_set_act_saved.argtypes = [vp, ip]
+        lib.moe_expert_counts_static.argtypes = [vp] * 4
         lib.moe_expert_ffn_fwd.argtypes = [vp, vp, ctypes.POINTER(_Layout)] + [vp] * 8
         lib.moe_combine.argtypes = [vp] * 6
         lib.moe_combine_bwd.argtypes = [vp] * 8
@@ -236,6 +237,11 @@ class Handle:
         i32 = torch.int32
         self._check(self.lib.moe_expert_counts(self._h, _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"),
                                                self._ws(), _stream()), "moe_expert_counts")
+
+    def expert_counts_static(self, idx, counts):
+        i32 = torch.int32
+        self._check(self.lib.moe_expert_counts_static(self._h, _ptr(idx, i32, self.A, "idx"), _ptr(counts, i32, self.E, "counts"),
+                                                      _stream()), "moe_expert_counts_static")
 
     def dispatch(self, expert_dest, X, idx, counts, layout: Layout, Xp, after_counts: bool = False):
         i32 = torch.int32

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoehot.so")
-UNITS = ["api", "gate", "gate_grad", "route", "rows", "plan", "ffn_f32", "ffn_bf16", "calib"]
+UNITS = ["api", "gate", "gate_grad", "route", "rows", "plan", "ffn_f32", "ffn_bf16", "noalloc", "calib"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -110,6 +110,7 @@ const char* moe_status_string(int status)
         case MOE_ERR_DTYPE: return "unsupported dtype";
         case MOE_ERR_UNIMPLEMENTED: return "not implemented";
         case MOE_ERR_HIP: return "HIP error";
+        case MOE_ERR_TOO_LARGE: return "input exceeds the capacity of the built-in scratch array";
         default: return "unknown status";
     }
 }

@@ -110,13 +110,18 @@ def test_trans_validates_arguments(lib):
     assert lib.moe_destroy(h) == 0
 
 
-def test_settings_validate_arguments(lib):
-    """moe_set_act_saved takes 0 or 1."""
+def test_static_counts_and_settings_validate_arguments(lib):
+    """The entry point without a workspace rejects inputs beyond its built-in array before anything is launched;
+    moe_set_act_saved takes 0 or 1."""
     from paper_2411_10003_amd.binding import _Shape
     vp = ctypes.c_void_p
     big = _Shape(1 << 22, 64, 128, 1024, 1, 4, 0, 2, 1, 0, 0)       # 16384 chunks x 1024 experts = 2^24 words
     h = ctypes.c_void_p()
     assert lib.moe_create(ctypes.byref(h), ctypes.byref(big)) == 0
+    assert lib.moe_expert_counts_static(h, vp(0x1000), vp(0x2000), None) == -8
+    assert lib.moe_expert_counts_static(h, None, vp(0x2000), None) == -1
+    assert lib.moe_expert_counts_static(None, vp(0x1000), vp(0x2000), None) == -1
+    assert b"scratch" in lib.moe_status_string(-8)
     assert lib.moe_set_act_saved(h, 2) == -2 and lib.moe_set_act_saved(h, 1) == 0 and lib.moe_set_act_saved(h, 0) == 0
     assert lib.moe_set_act_saved(None, 1) == -1
     assert lib.moe_destroy(h) == 0
