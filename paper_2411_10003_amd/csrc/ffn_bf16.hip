@@ -25,6 +25,17 @@
 #include "internal.h"
 #include <type_traits>
 
+// Where the main loop starts relative to a 256-byte boundary of the code, in 4-byte steps.  The loop is one basic
+// block that every wave runs tens of thousands of times; how its two phases fall into the instruction fetch
+// windows changes the time of the weight-gradient contraction by 6 % from the best to the worst placement (period:
+// 32 bytes) and of the others by 1-2 %, so the placement is fixed instead of being left to what precedes the loop.
+#ifndef LOOP_OFF
+#define LOOP_OFF 4
+#endif
+#define LOOP_OFF_STR2(x) #x
+#define LOOP_OFF_STR1(x) LOOP_OFF_STR2(x)
+#define LOOP_OFF_STR LOOP_OFF_STR1(LOOP_OFF)
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -48,6 +59,7 @@ struct GemmParams {
     const int32_t *slot_offsets, *dest_slots;
     int self, Gcap;
     int row_tiles, col_tiles;    // tile counts (row_tiles is an upper bound for NN/NT)
+    int band;                    // row tiles per band of the tile walk (a round of 32 tiles is band x 32/band)
     int n_tiles;
     // outputs
     bf16_t *O0, *O1, *O2;        // EPI_BF16: O0.  FWD1: Z, U, Act.  BWD1: dZ, dU, Act
@@ -69,8 +81,21 @@ __device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __ex
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
-#ifndef BAND
-#define BAND 8
+// Row tiles per band of the tile walk, per contraction (measured at d = 4096, h = 14336, SwiGLU; see launch()).
+#ifndef BAND_FWD1
+#define BAND_FWD1 16
+#endif
+#ifndef BAND_FWD2
+#define BAND_FWD2 8
+#endif
+#ifndef BAND_BWD1
+#define BAND_BWD1 8
+#endif
+#ifndef BAND_BWD2
+#define BAND_BWD2 8
+#endif
+#ifndef BAND_WGRAD
+#define BAND_WGRAD 8
 #endif
 constexpr int WGM = 2, WGN = 4, NWAVES = WGM * WGN, NT = NWAVES * 64;
 constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
@@ -184,6 +209,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     // that at any time the XCDs work on neighbouring rounds and what one of them has fetched from HBM
     // the others find in the memory-side cache.
     const int xcd = blockIdx.x & 7, q0 = blockIdx.x >> 3, q_stride = gridDim.x >> 3;
+    const int BAND = p.band;
     const int tiles_g = p.row_tiles * p.col_tiles;         // TN: tiles of one group
     const int n_act = total_rt * p.col_tiles;              // NN/NT: tiles that exist
     const int rpg = (tiles_g + q_stride - 1) / q_stride;   // TN: rounds per group
@@ -327,34 +353,41 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
 
     // Slices are requested strictly in order; the source offsets advance with the stream.
-    int iss_t = 0, iss_stage = 0;
+    int iss_stage = 0;
     int iss_seg = (KIND == KIND_TN) ? 0 : k_lo / k_per_seg, iss_in_seg = (KIND == KIND_TN) ? 0 : k_lo - iss_seg * k_per_seg;
     uint32_t soffA = (uint32_t)iss_in_seg * stepA, soffB = (uint32_t)iss_in_seg * stepB;
-    auto issue_next = [&]() {                              // slice iss_t -> stage iss_t % STAGES
+    // The requests of one slice into stage iss_stage, with the resources the caller has picked: no decision in it.
+    auto issue_with = [&](const rsrc_t ra, const rsrc_t rb0, const rsrc_t rb1) {
         const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
         iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
-        const rsrc_t ra = iss_seg ? rA[1] : rA[0];
 #pragma unroll
         for (int i = 0; i < PIECES; ++i) dma16(ra, st + ldsA[i], voffA[i], soffA);
-        if (DUAL) {
 #pragma unroll
-            for (int i = 0; i < PIECES; ++i) dma16(rB[i & 1], st + OPER_BYTES + ldsB[i], voffB[i], soffB);
-        } else {
-            const rsrc_t rb = (KIND == KIND_NT && iss_seg) ? rB[1] : rB[0];
-#pragma unroll
-            for (int i = 0; i < PIECES; ++i) dma16(rb, st + OPER_BYTES + ldsB[i], voffB[i], soffB);
-        }
-        ++iss_t; ++iss_in_seg;
+        for (int i = 0; i < PIECES; ++i) dma16((DUAL && (i & 1)) ? rb1 : rb0, st + OPER_BYTES + ldsB[i], voffB[i], soffB);
+        ++iss_in_seg;
         soffA += stepA; soffB += stepB;
+    };
+    // What may have to change between two slices: the next contraction segment (NN/NT), or, for TN, whose offset
+    // runs over all rows of the group, the base of the resources: buffer offsets are 32 bits, so the resources are
+    // moved up to the current slice long before that overflows (a group of 2^31 bytes and more).
+    auto issue_fixups = [&]() {
         if (KIND != KIND_TN && iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
-        // TN: the offset runs over all rows of the group.  Buffer offsets are 32 bits, so the resources
-        // are moved up to the current slice long before that overflows (a group of 2^31 bytes and more).
         if (KIND == KIND_TN && ((soffA | soffB) & 0xc0000000u)) {
             tn_baseA += soffA / 2; tn_bytesA -= soffA; soffA = 0;
             tn_baseB += soffB / 2; tn_bytesB -= soffB; soffB = 0;
             rA[0] = rA[1] = make_rsrc(tn_baseA, tn_bytesA);
             rB[0] = rB[1] = make_rsrc(tn_baseB, tn_bytesB);
         }
+    };
+    auto issue_next = [&]() {                              // one slice, strictly in order
+        issue_with(iss_seg ? rA[1] : rA[0], (KIND == KIND_NT && iss_seg) ? rB[1] : rB[0], rB[1]);
+        issue_fixups();
+    };
+    // how many slices can be requested from here without a fixup in between (at least one)
+    auto issue_run = [&]() -> int {
+        if (KIND != KIND_TN) return k_per_seg - iss_in_seg;
+        const uint32_t hi = soffA > soffB ? soffA : soffB, st = stepA > stepB ? stepA : stepB;
+        return (int)((0x3fffffffu - hi) / st) + 1;
     };
 
     // ---- per-lane fragment addresses inside a stage (step half 0; half 1 is a fixed distance away)
@@ -450,39 +483,55 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         constexpr int L = STAGES - 1;                      // slices requested ahead
         constexpr int SLICE_OPS = 2 * PIECES;              // DMA instructions of one wave per slice
-        auto wait_slices = [&](int n) {                    // at most n of this wave's slices still in flight
-            if (n >= 3) WAIT_VMCNT(3 * SLICE_OPS); else if (n == 2) WAIT_VMCNT(2 * SLICE_OPS);
-            else if (n == 1) WAIT_VMCNT(SLICE_OPS); else WAIT_VMCNT(0);
-        };
-        issue_next();
-        if (k_cnt > 1) issue_next();
-        if (k_cnt > 2) issue_next();
-        if (k_cnt > 3) issue_next();
-        wait_slices(min(L, k_cnt) - 1);                  // slice 0 has landed
+        // Every slice t is preceded by exactly t + L request groups of this wave (the prologue issues L of them,
+        // every slice one more), so "my pieces of slice t + 1 have landed" is always "at most L - 1 groups are still
+        // on their way": one fixed wait count for the whole contraction.  Where there is no slice left to request
+        // (a contraction shorter than the lookahead, and the last L slices of any contraction) the group goes to a
+        // resource of zero length: nothing is read, zeros land in a ring slot that nobody reads again.
+        const rsrc_t rnull = make_rsrc(p.A[0], 0);
+#pragma unroll
+        for (int i = 0; i < L; ++i) {
+            if (i < k_cnt) issue_next(); else issue_with(rnull, rnull, rnull);
+        }
+        WAIT_VMCNT((L - 1) * SLICE_OPS);                   // slice 0 has landed
         BLOCK_BARRIER();
         if (wm == 1) BLOCK_BARRIER();
         int cur = 0;
-        for (int t = 0; t < k_cnt; ++t) {
-            // fetch phase.  Ring slot (t+4) % 5 held slice t-1, which every wave finished reading at
-            // least one barrier ago.
-            load_frags(fa0, fb0, cur, std::integral_constant<int, 0>{});
-            load_frags(fa1, fb1, cur, std::integral_constant<int, 1>{});
-            __builtin_amdgcn_sched_barrier(0);
-            if (t + L < k_cnt) issue_next();
-            // this wave's pieces of slice t+1 must have landed before the barrier lets anyone read them
-            wait_slices(min(t + L, k_cnt - 1) - (t + 1));
-            wait_frags();
-            BLOCK_BARRIER();
-            // multiply phase
-            __builtin_amdgcn_s_setprio(1);
-            mma(fa0, fb0);
-            mma(fa1, fb1);
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            BLOCK_BARRIER();
-            cur = (cur + 1 == STAGES) ? 0 : cur + 1;
+        asm volatile(".p2align 8\n\t.rept " LOOP_OFF_STR "\n\ts_nop 0\n\t.endr" ::: "memory");
+        // One slice: fetch phase (fragments of slice t, then the requests for slice t + L, then the wait for this
+        // wave's pieces of slice t + 1), barrier, multiply phase, barrier.  Ring slot (t+4) % 5 held slice t-1,
+        // which every wave finished reading at least one barrier ago.  The loop has no decision in it: it runs
+        // over stretches of slices that need no fixup between their requests (a whole contraction segment, or
+        // all of a group's rows short of 2^30 bytes) with the resources of the stretch.
+        int t = 0;
+        while (t < k_cnt) {
+            const bool more = t + L < k_cnt;               // slices left to request
+            const int n = more ? min(k_cnt - L - t, issue_run()) : k_cnt - t;
+            const rsrc_t ra = more ? (iss_seg ? rA[1] : rA[0]) : rnull;
+            const rsrc_t rb0 = more ? ((KIND == KIND_NT && iss_seg) ? rB[1] : rB[0]) : rnull;
+            const rsrc_t rb1 = more ? rB[1] : rnull;
+            for (int i = 0; i < n; ++i) {
+                load_frags(fa0, fb0, cur, std::integral_constant<int, 0>{});
+                load_frags(fa1, fb1, cur, std::integral_constant<int, 1>{});
+                __builtin_amdgcn_sched_barrier(0);
+                issue_with(ra, rb0, rb1);
+                WAIT_VMCNT((L - 1) * SLICE_OPS);
+                wait_frags();
+                BLOCK_BARRIER();
+                __builtin_amdgcn_s_setprio(1);
+                mma(fa0, fb0);
+                mma(fa1, fb1);
+                __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                BLOCK_BARRIER();
+                cur = (cur + 1 == STAGES) ? 0 : cur + 1;
+            }
+            t += n;
+            if (more) issue_fixups();
         }
+        WAIT_VMCNT(0);                                     // the zero-length requests too: the epilogue reuses the ring
         if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
+        BLOCK_BARRIER();                                   // and everybody's requests have landed
     }
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");     // the last MFMAs have written back before the accumulators are read
@@ -716,6 +765,7 @@ hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
     hipError_t e;
     {   // fwd1: [rows, d] x W1[g] (d x h)
         GemmParams p = base_params(s, a);
+        p.band = BAND_FWD1;
         p.A[0] = (const bf16_t*)a.Xp; p.B[0] = (const bf16_t*)a.W1; p.B_dual = (const bf16_t*)a.W3;
         p.lda = d; p.ldb = h; p.b_group_stride = d * h; p.Kseg = s.d; p.N = s.h;
         p.O0 = (bf16_t*)a.Z; p.O1 = (bf16_t*)a.U; p.O2 = (bf16_t*)a.Act; p.ldo = h;
@@ -725,6 +775,7 @@ hipError_t launch_ffn_fwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
     }
     {   // fwd2: Act [rows, h] x W2[g] (h x d)
         GemmParams p = base_params(s, a);
+        p.band = BAND_FWD2;
         p.A[0] = (const bf16_t*)a.Act; p.B[0] = (const bf16_t*)a.W2;
         p.lda = h; p.ldb = d; p.b_group_stride = d * h; p.Kseg = s.h; p.N = s.d;
         p.O0 = (bf16_t*)a.Yp; p.ldo = d;
@@ -742,6 +793,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
     if (A > 0) {
         {   // bwd1: dA = dYp [rows, d] x W2[g]^T (W2 is h x d: contraction index contiguous)
             GemmParams p = base_params(s, a);
+            p.band = BAND_BWD1;
             p.A[0] = (const bf16_t*)a.dYp; p.B[0] = (const bf16_t*)a.W2;
             p.lda = d; p.ldb = d; p.b_group_stride = d * h; p.Kseg = s.d; p.N = s.h;
             p.O0 = (bf16_t*)a.dZ; p.O1 = (bf16_t*)a.dU; p.O2 = (bf16_t*)a.Act; p.ldo = h;
@@ -753,6 +805,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         }
         {   // bwd2: dXp = dZ [rows, h] x W1[g]^T (+ dU x W3[g]^T)
             GemmParams p = base_params(s, a);
+            p.band = BAND_BWD2;
             p.A[0] = (const bf16_t*)a.dZ; p.B[0] = (const bf16_t*)a.W1;
             p.A[1] = (const bf16_t*)a.dU; p.B[1] = (const bf16_t*)a.W3;
             p.n_seg = swiglu ? 2 : 1;
@@ -765,6 +818,7 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
     // weight gradients: contraction over the rows of each group
     auto wgrad = [&](const void* L, long ldl, int Mout, const void* R, long ldr, int N, float* out) {
         GemmParams p = base_params(s, a);
+        p.band = BAND_WGRAD;
         p.A[0] = (const bf16_t*)L; p.B[0] = (const bf16_t*)R;
         p.lda = ldl; p.ldb = ldr; p.b_group_stride = 0; p.Mout = Mout; p.N = N;
         p.OF = out; p.ldo = N; p.o_group_stride = d * h; p.accumulate = a.accumulate ? 1 : 0;

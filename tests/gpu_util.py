@@ -79,7 +79,8 @@ def assert_rows_close(got, want, tol: float, what: str = "", floor: float = 0.02
 # ---- which tiles the grouped matrix kernel works on (the test picks its samples from this; it mirrors the
 # kernel's tile walk: 256-row tiles from each group's first row, bands of 8 row tiles walked column by column,
 # and the tiles left after the last full round of the chip, which are split along the contraction)
-FFN_BM, FFN_BAND, FFN_SPLIT_UNITS = 256, 8, 320
+FFN_BM, FFN_SPLIT_UNITS = 256, 320
+FFN_BAND = {"fwd1": 16, "fwd2": 8, "bwd1": 8, "bwd2": 8}     # row tiles per band of each contraction's tile walk
 
 
 def ffn_row_tiles(group_rows):
@@ -91,7 +92,7 @@ def ffn_row_tiles(group_rows):
     return tiles
 
 
-def ffn_split_tiles(total_rt: int, col_tiles: int, k_slices: int, n_blocks: int):
+def ffn_split_tiles(total_rt: int, col_tiles: int, k_slices: int, n_blocks: int, band: int = 8):
     """(row tile, column tile) of the tiles the last, contraction-split round covers; empty if there is none."""
     n_act = total_rt * col_tiles
     n_full = (n_act // n_blocks) * n_blocks
@@ -103,10 +104,10 @@ def ffn_split_tiles(total_rt: int, col_tiles: int, k_slices: int, n_blocks: int)
         return []
     out = []
     for t in range(n_full, n_act):
-        band = t // (FFN_BAND * col_tiles)
-        in_band = t - band * FFN_BAND * col_tiles
-        band_rows = min(FFN_BAND, total_rt - band * FFN_BAND)
-        out.append((band * FFN_BAND + in_band % band_rows, in_band // band_rows))
+        b = t // (band * col_tiles)
+        in_band = t - b * band * col_tiles
+        band_rows = min(band, total_rt - b * band)
+        out.append((b * band + in_band % band_rows, in_band // band_rows))
     return out
 
 

@@ -60,7 +60,9 @@ def _check_pass(G, orc, case, hd, b, n_random=16, seed=0, label=""):
     swiglu = cfg.act == "swiglu"
     launches = {"fwd1": (-(-cfg.h // (128 if swiglu else 256)), cfg.d // 32), "fwd2": (-(-cfg.d // 256), cfg.h // 32),
                 "bwd1": (-(-cfg.h // 256), cfg.d // 32), "bwd2": (-(-cfg.d // 256), (2 if swiglu else 1) * cfg.h // 32)}
-    split = {n: G.ffn_split_tiles(len(row_tiles), ct, ks, n_blocks) for n, (ct, ks) in launches.items()}
+    split = {n: G.ffn_split_tiles(len(row_tiles), ct, ks, n_blocks, G.FFN_BAND[n]) for n, (ct, ks) in launches.items()}
+    for n, tiles in split.items():                               # every split tile lies in a sampled row tile
+        assert all(0 <= rt < len(row_tiles) for rt, _ in tiles), n
     a_s = case.sample_assignments(n_random, seed, every_tile=True)
     sampled_rows = np.sort(pos[a_s])
     for ti, (g, r0, r1) in enumerate(row_tiles):
