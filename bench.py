@@ -344,6 +344,22 @@ def main():
             e.update({"TFLOP/s": round(2 * fwd_flops / (call_ms[c] * 1e-3) / 1e12, 1)})
         per_call[c] = e
 
+    # ---- the gate on its own, back to back: in a step it starts while the memory-side cache still holds the dirty
+    # lines of the calls before it (268 MB of dX from moe_dispatch_bwd at config 3), whose write-back shares the HBM
+    # with the gate's reads and is billed to the gate's time; back to back there is none
+    if not args.step_only:
+        ge = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w)
+        torch.cuda.synchronize()
+        ge[0].record()
+        for _ in range(20):
+            hd.gate_topk(X, Wg, bg, b.logits, b.idx, b.w)
+        ge[1].record()
+        torch.cuda.synchronize()
+        g_ms = ge[0].elapsed_time(ge[1]) / 20
+        per_call["gate_topk"]["back_to_back_ms"] = round(g_ms, 4)
+        per_call["gate_topk"]["hbm_frac_back_to_back"] = round(hbm_bytes["gate_topk"] / (g_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+
     # ---- measured peaks of this GPU today: a plain streaming copy and a register-only bf16 MFMA loop
     measured_peak = None
     if not args.no_calib:
