@@ -170,6 +170,10 @@ def ffn_group_bounds(cfg, group_rows, backward: bool):
     peak = (PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS) * 1e12
     out = []
     for m in group_rows:
+        if m == 0:                       # nothing is read for an empty or unused group; its gradients are written as zeros
+            t_b = (nm * d * h * 4 if backward else 0) / (PEAK_HBM_GBS * 1e9)
+            out.append({"rows": 0, "bound_us": round(t_b * 1e6, 1), "bound": "hbm"})
+            continue
         flops = 2.0 * m * d * h * nm * (3 if backward else 1)
         w_bytes = nm * d * h * es
         # forward: Xp in, Z (and U) and the activation out, the activation in again, Yp out
@@ -548,7 +552,7 @@ def main():
         result["roofline"]["measured_peak"] = measured_peak
         if dt == "bf16":
             result["roofline"]["frac_of_measured"] = achieved / measured_peak["mfma_TFLOP/s"]
-    gb = ffn_group_bounds(cfg, group_rows, cfg.backward)
+    gb = ffn_group_bounds(cfg, group_rows + [0] * (cfg.G_max - len(group_rows)), cfg.backward)
     bound_ms = sum(x["bound_us"] for x in gb) / 1e3
     result["roofline"]["per_group"] = {"groups": gb, "sum_of_bounds_ms": round(bound_ms, 4),
                                        "frac_of_bound": round(bound_ms / ffn_ms, 4) if ffn_ms > 0 else None,
