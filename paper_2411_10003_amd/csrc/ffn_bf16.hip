@@ -76,7 +76,9 @@ __device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erf
 __device__ __forceinline__ float gelu_grad_f(float z) {
     return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
 }
-__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
+// exp and reciprocal are one instruction each (1 ulp); a full-precision division would be a dozen per element of an
+// epilogue whose vector instructions are what the matrix cores wait for between two tiles
+__device__ __forceinline__ float sigmoid_f(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
 // staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
@@ -564,6 +566,29 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     constexpr int ROWS_PER_PASS = 64 / CG;
     constexpr bool BWD1 = (EPI == EPI_BWD1_GELU || EPI == EPI_BWD1_SWIGLU);
     constexpr int N_PASS = 64 / ROWS_PER_PASS;
+    // The saved pre-activations of the backward epilogue are requested a batch of passes ahead, into the second
+    // of two register sets: a batch's loads are in flight while the batch before it is computed and stored, and,
+    // memory operations completing in the order of issue, no load ever waits for a store issued before it.
+#ifndef BWD1_BATCH
+#define BWD1_BATCH 2
+#endif
+    constexpr int BATCH = BWD1 ? BWD1_BATCH : N_PASS;
+    constexpr int NB = N_PASS / BATCH;                     // batches per 64-row half
+    static_assert(N_PASS % BATCH == 0, "batches tile the passes of a half");
+    uint4 zin[BWD1 ? 2 : 1][BWD1 ? BATCH : 1], uin[EPI == EPI_BWD1_SWIGLU ? 2 : 1][EPI == EPI_BWD1_SWIGLU ? BATCH : 1];
+    auto request = [&](int half, int pb, uint4* zi, uint4* ui) {
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+            // rows and columns past the end read the last valid ones (their results are not stored): no
+            // predicate, no zero fill
+            long row = (long)m0 + wm * WM + half * 64 + (pb + k) * ROWS_PER_PASS + erow;
+            row = row < row_limit ? row : row_limit - 1;
+            const int col = min(n0 + wn * WN + ecg * 8, p.N - 8);
+            zi[k] = *reinterpret_cast<const uint4*>(p.Zin + row * p.ldo + col);
+            if (EPI == EPI_BWD1_SWIGLU) ui[k] = *reinterpret_cast<const uint4*>(p.Uin + row * p.ldo + col);
+        }
+    };
+    if (BWD1) request(0, 0, zin[0], uin[0]);
 #pragma unroll
     for (int half = 0; half < TM / 2; ++half) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -591,24 +616,12 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
-        // the saved pre-activations of a batch of passes are requested at once, so that their latency
-        // is paid once per batch and not once per pass
-        constexpr int BATCH = (EPI == EPI_BWD1_SWIGLU) ? 4 : N_PASS;
 #pragma unroll
-        for (int pb = 0; pb < N_PASS; pb += BATCH) {
-        uint4 zin[BWD1 ? BATCH : 1], uin[EPI == EPI_BWD1_SWIGLU ? BATCH : 1];
+        for (int b = 0; b < NB; ++b) {
+        const int pb = b * BATCH, cur = (half * NB + b) & 1;
         if (BWD1) {
-#pragma unroll
-            for (int k = 0; k < BATCH; ++k) {
-                const long row = (long)m0 + wm * WM + half * 64 + (pb + k) * ROWS_PER_PASS + erow;
-                const int col = n0 + wn * WN + ecg * 8;
-                zin[k] = make_uint4(0, 0, 0, 0);
-                if (EPI == EPI_BWD1_SWIGLU) uin[k] = make_uint4(0, 0, 0, 0);
-                if (row < row_limit && col < p.N) {
-                    zin[k] = *reinterpret_cast<const uint4*>(p.Zin + row * p.ldo + col);
-                    if (EPI == EPI_BWD1_SWIGLU) uin[k] = *reinterpret_cast<const uint4*>(p.Uin + row * p.ldo + col);
-                }
-            }
+            const int nxt = half * NB + b + 1;
+            if (nxt < (TM / 2) * NB) request(nxt / NB, (nxt % NB) * BATCH, zin[cur ^ 1], uin[cur ^ 1]);
         }
 #pragma unroll
         for (int pass = pb; pass < pb + BATCH; ++pass) {
@@ -666,7 +679,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             } else if (EPI == EPI_BWD1_GELU) {
                 float z[8], dz[8], a[8];
-                unpack8(zin[pass - pb], z);
+                unpack8(zin[cur][pass - pb], z);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dz[e] = v[e] * gelu_grad_f(z[e]);
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
@@ -676,19 +689,26 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                     *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
                 }
             } else if (EPI == EPI_BWD1_SWIGLU) {
-                float z[8], uu[8], dz[8], du[8], a[8];
-                unpack8(zin[pass - pb], z);
-                unpack8(uin[pass - pb], uu);
+                // silu(z) = z s and silu'(z) = s + z s (1 - s) with s = sigmoid(z): eight vector instructions and
+                // two transcendentals per element (this epilogue is bound by its vector instructions)
+                float z[8], uu[8], dz[8], du[8], zs[8];
+                unpack8(zin[cur][pass - pb], z);
+                unpack8(uin[cur][pass - pb], uu);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float sg = sigmoid_f(z[e]);
-                    du[e] = v[e] * z[e] * sg;
-                    dz[e] = v[e] * uu[e] * sg * (1.0f + z[e] * (1.0f - sg));
-                    a[e] = z[e] * sg * uu[e];
+                    zs[e] = z[e] * sg;
+                    du[e] = v[e] * zs[e];
+                    dz[e] = (v[e] * uu[e]) * __builtin_fmaf(zs[e], 1.0f - sg, sg);
                 }
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
                 *reinterpret_cast<uint4*>(p.O1 + o) = pack8(du);
-                if (p.write_act) *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                if (p.write_act) {
+                    float a[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) a[e] = zs[e] * uu[e];
+                    *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                }
             }
         }
         }
