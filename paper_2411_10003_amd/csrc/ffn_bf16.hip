@@ -72,10 +72,28 @@ struct GemmParams {
     int split_cap;               // units that fit there
 };
 
-__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_grad_f(float z) {
-    return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+// GELU (Eq. 2 with the Gaussian CDF) and its derivative from one exponential and one reciprocal: erf by the
+// five-term rational approximation of Abramowitz & Stegun 7.1.26 (absolute error below 1.5e-7, two orders under
+// what a bf16 output resolves), whose exp(-x^2) at x = z / sqrt(2) is also the density the derivative needs.  The
+// library erff is some thirty instructions with branches, per element of an epilogue that the matrix cores wait for.
+struct gelu_parts { float cdf, pdf; };                     // Phi(z) and phi(z)
+__device__ __forceinline__ gelu_parts gelu_terms(float z)
+{
+    const float x = z * 0.70710678118654752f, ax = __builtin_fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, ax, 1.0f));
+    const float e = __expf(-(ax * ax));                    // exp(-z^2 / 2)
+    float y = __builtin_fmaf(1.061405429f, t, -1.453152027f);
+    y = __builtin_fmaf(y, t, 1.421413741f);
+    y = __builtin_fmaf(y, t, -0.284496736f);
+    y = __builtin_fmaf(y, t, 0.254829592f);
+    const float half_erfc = 0.5f * (y * t) * e;            // (1 - erf|x|) / 2
+    gelu_parts r;
+    r.cdf = z < 0.0f ? half_erfc : 1.0f - half_erfc;
+    r.pdf = 0.3989422804014327f * e;
+    return r;
 }
+__device__ __forceinline__ float gelu_f(float z) { return z * gelu_terms(z).cdf; }
+__device__ __forceinline__ float gelu_grad_f(float z) { const gelu_parts g = gelu_terms(z); return __builtin_fmaf(z, g.pdf, g.cdf); }
 // exp and reciprocal are one instruction each (1 ulp); a full-precision division would be a dozen per element of an
 // epilogue whose vector instructions are what the matrix cores wait for between two tiles
 __device__ __forceinline__ float sigmoid_f(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
