@@ -64,8 +64,6 @@ struct GemmParams {
     // outputs
     bf16_t *O0, *O1, *O2;        // EPI_BF16: O0.  FWD1: Z, U, Act.  BWD1: dZ, dU, Act
     float* OF;                   // EPI_F32
-    float* OF2;                  // TN: output of a second product that shares the A operand (B[1] is its B), or null
-    int prod_cols;               // TN: column tiles per product (set by launch())
     int accumulate;              // EPI_F32: add to the output instead of overwriting it
     long ldo, o_group_stride;
     const bf16_t *Zin, *Uin;     // BWD1: saved pre-activations
@@ -256,7 +254,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 
   for (int q = q_first; q < q_end; q += q_step) {
     int g, rt, ct;
-    int prod = 0;                // TN: which of the launch's products the tile belongs to
     int part = 0, parts = 1, unit = 0;                     // K-split: which part of how many, and where it is kept
     long a_row0, a_row_end;      // valid rows of the A tile (NN/NT) or of the contraction (TN)
     int k_tiles;
@@ -274,7 +271,6 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         const int band_rows = min(BAND, p.row_tiles - band * BAND);
         rt = band * BAND + in_band % band_rows;
         ct = in_band / band_rows;
-        if (ct >= p.prod_cols) { prod = 1; ct -= p.prod_cols; }           // the second product's column tiles follow the first's
         const int row0 = __builtin_amdgcn_readlane(g_row0, g & 63);       // empty for unused groups
         const int rows = __builtin_amdgcn_readlane(g_rows, g & 63);
         a_row0 = row0; a_row_end = row0 + rows;
@@ -321,7 +317,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         const long a_rows = a_row_end - a_row0;
         if (KIND == KIND_TN) {
             tn_baseA = p.A[0] + a_row0 * p.lda + m0; tn_bytesA = (a_rows * p.lda - m0) * 2;
-            tn_baseB = p.B[prod] + a_row0 * p.ldb + n0; tn_bytesB = (a_rows * p.ldb - n0) * 2;
+            tn_baseB = p.B[0] + a_row0 * p.ldb + n0; tn_bytesB = (a_rows * p.ldb - n0) * 2;
             rA[0] = rA[1] = make_rsrc(tn_baseA, tn_bytesA);
             rB[0] = rB[1] = make_rsrc(tn_baseB, tn_bytesB);
             stepA = (uint32_t)(BK * p.lda * 2);
@@ -678,7 +674,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             if (EPI == EPI_BF16) {
                 *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
             } else if (EPI == EPI_F32) {
-                float* dst = (prod ? p.OF2 : p.OF) + (long)g * p.o_group_stride + o;
+                float* dst = p.OF + (long)g * p.o_group_stride + o;
                 if (p.accumulate) {
                     const float4 o0 = *reinterpret_cast<const float4*>(dst), o1 = *reinterpret_cast<const float4*>(dst + 4);
                     v[0] += o0.x; v[1] += o0.y; v[2] += o0.z; v[3] += o0.w;
@@ -746,8 +742,6 @@ hipError_t launch(GemmParams p, int rows_upper, int n_groups_cap, hipStream_t st
     constexpr bool DUAL = (EPI == EPI_FWD1_SWIGLU);
     const int bn = DUAL ? BN / 2 : BN;
     p.col_tiles = (p.N + bn - 1) / bn;
-    p.prod_cols = p.col_tiles;
-    if (KIND == KIND_TN && p.OF2 != nullptr) p.col_tiles *= 2;
     if (KIND == KIND_TN) {
         p.row_tiles = (p.Mout + BM - 1) / BM;
         p.n_tiles = n_groups_cap * p.row_tiles * p.col_tiles;
@@ -860,27 +854,19 @@ hipError_t launch_ffn_bwd_bf16(const moe_shape_t& s, const ffn_args& a, hipStrea
         }
     }
     // weight gradients: contraction over the rows of each group
-    // Two products that share their left operand go into one launch, the column tiles of the second after those of
-    // the first inside every band: dW1 = Xp^T dZ and dW3 = Xp^T dU.  Besides the shared operand this doubles the
-    // tiles of a group, and a group whose tiles are not a multiple of the chip's blocks leaves the XCDs uneven.
-    auto wgrad = [&](const void* L, long ldl, int Mout, const void* R, const void* R2, long ldr, int N, float* out, float* out2) {
+    auto wgrad = [&](const void* L, long ldl, int Mout, const void* R, long ldr, int N, float* out) {
         GemmParams p = base_params(s, a);
         p.band = BAND_WGRAD;
-        p.A[0] = (const bf16_t*)L; p.B[0] = (const bf16_t*)R; p.B[1] = (const bf16_t*)R2;
+        p.A[0] = (const bf16_t*)L; p.B[0] = (const bf16_t*)R;
         p.lda = ldl; p.ldb = ldr; p.b_group_stride = 0; p.Mout = Mout; p.N = N;
-        p.OF = out; p.OF2 = out2; p.ldo = N; p.o_group_stride = d * h; p.accumulate = a.accumulate ? 1 : 0;
+        p.OF = out; p.ldo = N; p.o_group_stride = d * h; p.accumulate = a.accumulate ? 1 : 0;
         return launch<KIND_TN, EPI_F32>(p, A, s.G, st);
     };
-#ifdef WGRAD_SEPARATE
-    e = wgrad(a.Xp, d, s.d, a.dZ, nullptr, h, s.h, a.dW1, nullptr);
+    e = wgrad(a.Xp, d, s.d, a.dZ, h, s.h, a.dW1);
     if (e != hipSuccess) return e;
     if (swiglu) {
-        e = wgrad(a.Xp, d, s.d, a.dU, nullptr, h, s.h, a.dW3, nullptr);
+        e = wgrad(a.Xp, d, s.d, a.dU, h, s.h, a.dW3);
         if (e != hipSuccess) return e;
     }
-#else
-    e = swiglu ? wgrad(a.Xp, d, s.d, a.dZ, a.dU, h, s.h, a.dW1, a.dW3) : wgrad(a.Xp, d, s.d, a.dZ, nullptr, h, s.h, a.dW1, nullptr);
-    if (e != hipSuccess) return e;
-#endif
-    return wgrad(a.Act, h, s.h, a.dYp, nullptr, d, s.d, a.dW2, nullptr);
+    return wgrad(a.Act, h, s.h, a.dYp, d, s.d, a.dW2);
 }
