@@ -265,7 +265,8 @@ def main():
         hd.expert_counts(b.idx, b.counts); mark(2)
         # counts -> dispatch on the same idx and workspace with nothing in between: the histograms are not rebuilt
         hd.dispatch_after_counts(expert_dest, X, b.idx, b.counts, b.layout, b.Xp); mark(3)
-        hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z, b.U); mark(4)
+        # a forward-only workload does not keep the pre-activations (nothing reads them)
+        hd.expert_ffn_fwd(b.Xp, b.layout, W1, W2, W3, b.Yp, b.Z if cfg.backward else None, b.U if cfg.backward else None); mark(4)
         hd.combine(b.Yp, b.layout.pos, b.w, b.out); mark(5)
         if cfg.backward:
             hd.combine_bwd(dOut, b.Yp, b.layout.pos, b.w, b.dYp, b.dw); mark(6)
@@ -548,6 +549,7 @@ def main():
         "per_call": per_call,
     }
     result["config"]["act_saved"] = bool(act_saved)
+    result["config"]["pre_activations_kept"] = bool(cfg.backward)
     if measured_peak is not None:
         result["roofline"]["measured_peak"] = measured_peak
         if dt == "bf16":

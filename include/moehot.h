@@ -159,7 +159,10 @@ int moe_dispatch_after_counts(moe_handle_t h, const int32_t* expert_dest, const 
  *   in : Xp[A,d] elt; layout (slot_offsets, dest_slots are read); W1[G,d,h], W2[G,h,d] elt,
  *        W3[G,d,h] elt for SwiGLU (NULL otherwise)
  *   out: rows of the hosted groups only: Yp[A,d] elt, Z[A,h] elt (= Xp W1, kept for backward),
- *        U[A,h] elt (= Xp W3, SwiGLU only, else NULL).  Other rows are not touched. */
+ *        U[A,h] elt (= Xp W3, SwiGLU only, else NULL).  Other rows are not touched.
+ * Forward only (inference): Z = NULL and U = NULL; the pre-activations are then not written (a third of the
+ * first contraction's stores for GELU, two thirds for SwiGLU) and Yp holds the same bits as with them.  Z and U
+ * are given or left out together (MOE_ERR_NULL otherwise); a backward call needs a forward call that kept them. */
 int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* layout,
                        const void* W1, const void* W2, const void* W3,
                        void* Yp, void* Z, void* U, void* ws, void* stream);

@@ -194,10 +194,11 @@ int moe_expert_ffn_fwd(moe_handle_t h, const void* Xp, const moe_layout_t* L,
                        const void* W1, const void* W2, const void* W3,
                        void* Yp, void* Z, void* U, void* ws, void* stream)
 {
-    if (!h || !Xp || !L || !W1 || !W2 || !Yp || !Z) return MOE_ERR_NULL;
+    if (!h || !Xp || !L || !W1 || !W2 || !Yp) return MOE_ERR_NULL;
     if (!L->slot_offsets || !L->dest_slots) return MOE_ERR_NULL;
     const bool swiglu = h->s.act == MOE_ACT_SWIGLU;
-    if (swiglu && (!W3 || !U)) return MOE_ERR_NULL;
+    if (swiglu && !W3) return MOE_ERR_NULL;
+    if (swiglu && ((Z == nullptr) != (U == nullptr))) return MOE_ERR_NULL;     // kept together or not at all
     if (!ws || misaligned(ws)) return MOE_ERR_WORKSPACE;
     const Carve c{(char*)ws, h};
     ffn_args a{};

@@ -686,14 +686,16 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 float a[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = gelu_f(v[e]);
-                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+                if (p.O0) *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);       // forward only: Z is not kept
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             } else if (EPI == EPI_FWD1_SWIGLU) {
                 float a[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = v[e] * sigmoid_f(v[e]) * u[e];
-                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
-                *reinterpret_cast<uint4*>(p.O1 + o) = pack8(u);
+                if (p.O0) {                                                      // forward only: Z and U are not kept
+                    *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+                    *reinterpret_cast<uint4*>(p.O1 + o) = pack8(u);
+                }
                 *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
             } else if (EPI == EPI_BWD1_GELU) {
                 float z[8], dz[8], a[8];

@@ -98,8 +98,8 @@ __global__ __launch_bounds__(TS * TS) void ffn_f32_kernel(F32Args a)
         View B2{swiglu ? a.W3 + wdh : a.W1 + wdh, h, 1};
         tile_gemm(A, B, A, B2, swiglu, m, n, rows, h, d, acc, acc2);
         if (m < rows && n < h) {
-            a.Z[r * h + n] = acc;
-            if (swiglu) { a.U[r * h + n] = acc2; a.Act[r * h + n] = acc * sigmoid_f(acc) * acc2; }
+            if (a.Z) a.Z[r * h + n] = acc;              // forward only: the pre-activations are not kept
+            if (swiglu) { if (a.U) a.U[r * h + n] = acc2; a.Act[r * h + n] = acc * sigmoid_f(acc) * acc2; }
             else a.Act[r * h + n] = gelu_f(acc);
         }
     } else if (MODE == FWD2) {

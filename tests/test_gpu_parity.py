@@ -276,6 +276,18 @@ def test_ffn_forward_and_combine(G, orc, cfg):
     torch.cuda.synchronize()
     want = orc.combine(case.oracle_Yp_full(), pos, case.route["w"], cfg.k)
     G.assert_rows_close(G.host(b.out), want, tol, "b.out")
+    # forward only: without Z and U the output holds the same bits and the two buffers are not written
+    Yp_kept = b.Yp.clone()
+    b.Yp.fill_(3.0); b.Z.fill_(5.0)
+    if b.U is not None:
+        b.U.fill_(5.0)
+    hd.expert_ffn_fwd(b.Xp, b.layout, case.dW1, case.dW2, case.dW3, b.Yp, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(b.Yp[torch.as_tensor(rows, device=b.Yp.device).long()], Yp_kept[torch.as_tensor(rows, device=b.Yp.device).long()])
+    assert bool((b.Z == 5.0).all()) and (b.U is None or bool((b.U == 5.0).all()))
+    if cfg.act == "swiglu":                                    # kept together or not at all
+        with pytest.raises(G.binding.MoeError):
+            hd.expert_ffn_fwd(b.Xp, b.layout, case.dW1, case.dW2, case.dW3, b.Yp, b.Z, None)
 
 
 def test_identity_experts_return_x_times_weight_sum(G):
