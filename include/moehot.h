@@ -59,7 +59,7 @@ typedef enum { MOE_ACT_GELU = 0, MOE_ACT_SWIGLU = 1 } moe_act_t;
  *   G      : capacity of the hosted weight arrays (owned + replicated experts), 1 <= G <= E.
  *   renorm : 1 = the k gate weights of a token are renormalised to sum to one.
  * Limits: 1 <= k <= 8, k <= E <= 1024, 1 <= P <= E; MOE_BF16 needs d % 64 == 0, h % 64 == 0,
- * G <= 64 (hosted weight groups) and d*h < 2^30 (one weight matrix under 2 GiB);
+ * G <= 64 (hosted weight groups), d*h < 2^30 (one weight matrix under 2 GiB) and d, h < 2^22;
  * T*k < 2^30; T*k*max(d, h) may exceed 2^31 (row offsets are 64-bit). */
 typedef struct {
     int T, d, h, E, k, P, self, G;

@@ -32,6 +32,8 @@ int check_shape(const moe_shape_t& s)
     if (s.renorm != 0 && s.renorm != 1) return MOE_ERR_SHAPE;
     if ((long long)s.T * s.k >= (1ll << 31) / 2) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_BF16 && (s.d % 64 != 0 || s.h % 64 != 0)) return MOE_ERR_SHAPE;
+    // the bf16 epilogues address a 256-row tile of an output with 32-bit byte offsets
+    if (s.dtype == MOE_BF16 && (s.d >= (1 << 22) || s.h >= (1 << 22))) return MOE_ERR_SHAPE;
     if (s.dtype == MOE_BF16 && s.G > 64) return MOE_ERR_SHAPE;      // the grouped GEMM keeps one group per lane
     if (s.dtype == MOE_BF16 && (long long)s.d * s.h >= (1ll << 30)) return MOE_ERR_SHAPE;   // 32-bit byte offsets inside one weight matrix
     if (s.dtype == MOE_F32 && (s.d % 4 != 0)) return MOE_ERR_SHAPE;

@@ -122,7 +122,8 @@ constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
 constexpr int PIECES = 16 / NWAVES;         // 1-KB DMA pieces per wave per 16-KB operand slice
 constexpr uint32_t OPER_BYTES = 16384, STAGE_BYTES = 2 * OPER_BYTES;
 constexpr int EP_PITCH = WN * 4 + 16;       // epilogue patch: bytes per staged row of WN floats (padded against bank conflicts)
-constexpr int EP_WAVE = 64 * EP_PITCH;      // 64 rows per wave at a time
+constexpr int EP_ROWS = 32;               // rows a wave stages at a time: one row of fragments
+constexpr int EP_WAVE = EP_ROWS * EP_PITCH;
 constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_BYTES;
 constexpr size_t LDS_BYTES = RING_BYTES > (size_t)NWAVES * EP_WAVE ? RING_BYTES : (size_t)NWAVES * EP_WAVE;
 
@@ -158,6 +159,8 @@ __device__ __forceinline__ void lds_frag_kmajor_at(bf16x8& f, uint32_t addr)
 }
 
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;     // raw buffer resource (4 scalar registers)
+typedef __amdgpu_buffer_rsrc_t buf_rsrc_t;                   // the same thing as the store builtin wants it
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, long long bytes)
 {
@@ -572,18 +575,34 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     }
     // ---- epilogue.  A lane holds, per fragment, row l%32 and columns q*8 + (l/32)*4 + 0..3: storing
     // from there would touch 16-byte pieces of 32 different rows per instruction.  Instead every wave
-    // passes its 128 x 64 accumulators through its own LDS patch (64 rows at a time, fp32) and reads
-    // them back row-major, 8 consecutive columns per lane, so that global loads and stores move whole
-    // 128/256-byte row segments.  The ring is free: the last barrier of the loop has been passed and
-    // every DMA has landed.
-    unsigned char* patch = smem + wave * EP_WAVE;
+    // passes its 128 x 64 accumulators through its own LDS patch (one row of fragments, 32 rows, at a time,
+    // fp32) and reads them back row-major, 8 consecutive columns per lane, so that global loads and stores
+    // move whole 128/256-byte row segments.  The patches lie at the top of LDS, above ring slots 0 and 1.
+    unsigned char* patch = smem + (LDS_BYTES - (size_t)NWAVES * EP_WAVE) + wave * EP_WAVE;
     const int lrow = lane & 31, lcol = (lane >> 5) * 4;
     const long row_limit = (KIND == KIND_TN) ? (long)p.Mout : a_row_end;
     constexpr int CG = DUAL ? WN / 16 : WN / 8;            // 8-column groups per staged row that carry outputs
     const int erow = lane / CG, ecg = lane % CG;
     constexpr int ROWS_PER_PASS = 64 / CG;
     constexpr bool BWD1 = (EPI == EPI_BWD1_GELU || EPI == EPI_BWD1_SWIGLU);
-    constexpr int N_PASS = 64 / ROWS_PER_PASS;
+    constexpr int N_PASS = EP_ROWS / ROWS_PER_PASS;        // passes per staged row of fragments
+    // NN/NT: every store of the epilogue is issued whatever the tile looks like, as a buffer store whose resource
+    // ends with the tile's last valid row (or has no length at all, for an output that is not written): the number
+    // of memory instructions of an epilogue is then a constant of the instantiation, which the waits for the next
+    // tile's first slices count on (see the main loop).  TN keeps ordinary predicated stores.
+    constexpr bool UNCOND = (KIND != KIND_TN);
+    const int wcol0 = n0 + (DUAL ? wn * (WN / 2) : wn * WN);           // first column of this wave: all of its columns exist or none
+    buf_rsrc_t rO0 = buf_rsrc_t(), rO1 = buf_rsrc_t(), rO2 = buf_rsrc_t();
+    if (UNCOND) {
+        const bool cols = wcol0 < p.N;
+        const int bytes = (int)((row_limit - m0) * p.ldo * 2);
+        auto out_rsrc = [&](bf16_t* base, bool on) {
+            return __builtin_amdgcn_make_buffer_rsrc((void*)(base ? base + (long)m0 * p.ldo : p.O2), 0, (on && base && cols) ? bytes : 0, 0x00020000);
+        };
+        rO0 = out_rsrc(p.O0, true);
+        rO1 = out_rsrc(p.O1, EPI == EPI_FWD1_SWIGLU || EPI == EPI_BWD1_SWIGLU);
+        rO2 = out_rsrc(p.O2, BWD1 ? p.write_act != 0 : (EPI == EPI_FWD1_GELU || EPI == EPI_FWD1_SWIGLU));
+    }
     // The saved pre-activations of the backward epilogue are requested a batch of passes ahead, into the second
     // of two register sets: a batch's loads are in flight while the batch before it is computed and stored, and,
     // memory operations completing in the order of issue, no load ever waits for a store issued before it.
@@ -591,15 +610,15 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
 #define BWD1_BATCH 2
 #endif
     constexpr int BATCH = BWD1 ? BWD1_BATCH : N_PASS;
-    constexpr int NB = N_PASS / BATCH;                     // batches per 64-row half
-    static_assert(N_PASS % BATCH == 0, "batches tile the passes of a half");
+    constexpr int NB = N_PASS / BATCH;                     // batches per staged row of fragments
+    static_assert(N_PASS % BATCH == 0, "batches tile the passes of a staged row of fragments");
     uint4 zin[BWD1 ? 2 : 1][BWD1 ? BATCH : 1], uin[EPI == EPI_BWD1_SWIGLU ? 2 : 1][EPI == EPI_BWD1_SWIGLU ? BATCH : 1];
-    auto request = [&](int half, int pb, uint4* zi, uint4* ui) {
+    auto request = [&](int fr, int pb, uint4* zi, uint4* ui) {
 #pragma unroll
         for (int k = 0; k < BATCH; ++k) {
             // rows and columns past the end read the last valid ones (their results are not stored): no
             // predicate, no zero fill
-            long row = (long)m0 + wm * WM + half * 64 + (pb + k) * ROWS_PER_PASS + erow;
+            long row = (long)m0 + wm * WM + fr * EP_ROWS + (pb + k) * ROWS_PER_PASS + erow;
             row = row < row_limit ? row : row_limit - 1;
             const int col = min(n0 + wn * WN + ecg * 8, p.N - 8);
             zi[k] = *reinterpret_cast<const uint4*>(p.Zin + row * p.ldo + col);
@@ -608,45 +627,44 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     };
     if (BWD1) request(0, 0, zin[0], uin[0]);
 #pragma unroll
-    for (int half = 0; half < TM / 2; ++half) {
+    for (int fr = 0; fr < TM; ++fr) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& a = acc[fr][j];
+                float4 val = make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
+                if (KIND != KIND_TN && FIN) {                  // the parts of a split tile, added in ascending order
+                    const float4* ws4 = reinterpret_cast<const float4*>(p.split_ws) + ((size_t)unit * NWAVES + wave) * (TM * TN * 4) * 64 + lane;
+                    float4 v[4];                               // at most 4 parts; all loads independent of each other
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x16& a = acc[half * 2 + ii][j];
-                    float4 val = make_float4(a[q * 4 + 0], a[q * 4 + 1], a[q * 4 + 2], a[q * 4 + 3]);
-                    if (KIND != KIND_TN && FIN) {                  // the parts of a split tile, added in ascending order
-                        const float4* ws4 = reinterpret_cast<const float4*>(p.split_ws) + ((size_t)unit * NWAVES + wave) * (TM * TN * 4) * 64 + lane;
-                        float4 v[4];                               // at most 4 parts; all loads independent of each other
+                    for (int s = 0; s < 4; ++s)
+                        v[s] = (s < parts) ? ws4[(size_t)s * NWAVES * (TM * TN * 4) * 64 + ((fr * TN + j) * 4 + q) * 64]
+                                           : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    val = v[0];
 #pragma unroll
-                        for (int s = 0; s < 4; ++s)
-                            v[s] = (s < parts) ? ws4[(size_t)s * NWAVES * (TM * TN * 4) * 64 + (((half * 2 + ii) * TN + j) * 4 + q) * 64]
-                                               : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                        val = v[0];
-#pragma unroll
-                        for (int s = 1; s < 4; ++s) { val.x += v[s].x; val.y += v[s].y; val.z += v[s].z; val.w += v[s].w; }
-                    }
-                    *reinterpret_cast<float4*>(patch + (ii * 32 + lrow) * EP_PITCH + (j * 32 + q * 8 + lcol) * 4) = val;
+                    for (int s = 1; s < 4; ++s) { val.x += v[s].x; val.y += v[s].y; val.z += v[s].z; val.w += v[s].w; }
                 }
+                *reinterpret_cast<float4*>(patch + lrow * EP_PITCH + (j * 32 + q * 8 + lcol) * 4) = val;
+            }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-        const int pb = b * BATCH, cur = (half * NB + b) & 1;
+        const int pb = b * BATCH, cur = (fr * NB + b) & 1;
         if (BWD1) {
-            const int nxt = half * NB + b + 1;
-            if (nxt < (TM / 2) * NB) request(nxt / NB, (nxt % NB) * BATCH, zin[cur ^ 1], uin[cur ^ 1]);
+            const int nxt = fr * NB + b + 1;
+            if (nxt < TM * NB) request(nxt / NB, (nxt % NB) * BATCH, zin[cur ^ 1], uin[cur ^ 1]);
         }
 #pragma unroll
         for (int pass = pb; pass < pb + BATCH; ++pass) {
-            const int r = pass * ROWS_PER_PASS + erow;                     // row inside the 64-row patch
-            const long row = (long)m0 + wm * WM + half * 64 + r;
-            const int col = n0 + (DUAL ? wn * (WN / 2) : wn * WN) + ecg * 8;
-            if (row >= row_limit || col >= p.N) continue;
+            const int r = pass * ROWS_PER_PASS + erow;                     // row inside the patch
+            const int trow = wm * WM + fr * EP_ROWS + r;                   // row inside the tile
+            const long row = (long)m0 + trow;
+            const int col = wcol0 + ecg * 8;
+            if (!UNCOND && (row >= row_limit || col >= p.N)) continue;
             float v[8], u[8];
             {
                 // dual: fragments alternate x W1 / x W3, 32 columns each; group ecg sits in pair ecg/4
@@ -662,6 +680,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 u[0] = x0.x; u[1] = x0.y; u[2] = x0.z; u[3] = x0.w; u[4] = x1.x; u[5] = x1.y; u[6] = x1.z; u[7] = x1.w;
             }
             const long o = row * p.ldo + col;
+            const int bo = (int)(((long)trow * p.ldo + col) * 2);          // byte offset from the tile's first row
             auto pack8 = [](const float* f) {
                 return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
             };
@@ -671,8 +690,11 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 f[4] = __uint_as_float(w.z << 16); f[5] = __uint_as_float(w.z & 0xffff0000u);
                 f[6] = __uint_as_float(w.w << 16); f[7] = __uint_as_float(w.w & 0xffff0000u);
             };
+            auto put = [&](buf_rsrc_t r, const uint4 w) {      // rows past the tile's last one fall outside the resource
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, w), r, bo, 0, 0);
+            };
             if (EPI == EPI_BF16) {
-                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
+                put(rO0, pack8(v));
             } else if (EPI == EPI_F32) {
                 float* dst = p.OF + (long)g * p.o_group_stride + o;
                 if (p.accumulate) {
@@ -686,28 +708,29 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 float a[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = gelu_f(v[e]);
-                if (p.O0) *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);       // forward only: Z is not kept
-                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                put(rO0, pack8(v));                            // no length in a forward-only pass: Z is not kept
+                put(rO2, pack8(a));
             } else if (EPI == EPI_FWD1_SWIGLU) {
                 float a[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] = v[e] * sigmoid_f(v[e]) * u[e];
-                if (p.O0) {                                                      // forward only: Z and U are not kept
-                    *reinterpret_cast<uint4*>(p.O0 + o) = pack8(v);
-                    *reinterpret_cast<uint4*>(p.O1 + o) = pack8(u);
-                }
-                *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                put(rO0, pack8(v));                            // no length in a forward-only pass: Z and U are not kept
+                put(rO1, pack8(u));
+                put(rO2, pack8(a));
             } else if (EPI == EPI_BWD1_GELU) {
-                float z[8], dz[8], a[8];
+                float z[8], dz[8];
                 unpack8(zin[cur][pass - pb], z);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dz[e] = v[e] * gelu_grad_f(z[e]);
-                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
+                uint4 aw = make_uint4(0, 0, 0, 0);
                 if (p.write_act) {
+                    float a[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) a[e] = gelu_f(z[e]);
-                    *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                    aw = pack8(a);
                 }
+                put(rO0, pack8(dz));
+                put(rO2, aw);                                  // no length when the forward pass's activation is still there
             } else if (EPI == EPI_BWD1_SWIGLU) {
                 // silu(z) = z s and silu'(z) = s + z s (1 - s) with s = sigmoid(z): eight vector instructions and
                 // two transcendentals per element (this epilogue is bound by its vector instructions)
@@ -721,14 +744,16 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                     du[e] = v[e] * zs[e];
                     dz[e] = (v[e] * uu[e]) * __builtin_fmaf(zs[e], 1.0f - sg, sg);
                 }
-                *reinterpret_cast<uint4*>(p.O0 + o) = pack8(dz);
-                *reinterpret_cast<uint4*>(p.O1 + o) = pack8(du);
+                uint4 aw = make_uint4(0, 0, 0, 0);
                 if (p.write_act) {
                     float a[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) a[e] = zs[e] * uu[e];
-                    *reinterpret_cast<uint4*>(p.O2 + o) = pack8(a);
+                    aw = pack8(a);
                 }
+                put(rO0, pack8(dz));
+                put(rO1, pack8(du));
+                put(rO2, aw);                                  // no length when the forward pass's activation is still there
             }
         }
         }
