@@ -595,7 +595,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     buf_rsrc_t rO0 = buf_rsrc_t(), rO1 = buf_rsrc_t(), rO2 = buf_rsrc_t();
     if (UNCOND) {
         const bool cols = wcol0 < p.N;
-        const int bytes = (int)((row_limit - m0) * p.ldo * 2);
+        const long vrows = row_limit - m0 < BM ? row_limit - m0 : BM;       // the group may go on for millions of rows
+        const int bytes = (int)(vrows * p.ldo * 2);
         auto out_rsrc = [&](bf16_t* base, bool on) {
             return __builtin_amdgcn_make_buffer_rsrc((void*)(base ? base + (long)m0 * p.ldo : p.O2), 0, (on && base && cols) ? bytes : 0, 0x00020000);
         };
