@@ -335,9 +335,12 @@ int moe_plan(const moe_planner_t* cfg, const int32_t* gating, const moe_plan_out
  * matrix instructions (32768 flop each) on operands held in registers: what the matrix cores sustain at this
  * GPU's power limit, to set beside the published peak.  out: device, out_floats floats of which the first
  * blocks x threads are written (so that the work cannot be optimised away; MOE_ERR_SHAPE if there are fewer:
- * 512 per compute unit are enough); *blocks and *threads (host) receive the launch shape. */
+ * 512 per compute unit are enough); *blocks and *threads (host) receive the launch shape.
+ * moe_calib_round_bf16: out[i] = in[i] rounded to bf16 exactly as every bf16 output of the library is rounded
+ * (round to nearest, ties to even; NaN stays NaN): n floats in, n 16-bit words out, device pointers. */
 int moe_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
 int moe_calib_mfma(float* out, size_t out_floats, int iters, int* blocks, int* threads, void* stream);
+int moe_calib_round_bf16(const float* in, uint16_t* out, size_t n, void* stream);
 
 #ifdef __cplusplus
 }

@@ -26,6 +26,7 @@ EXPORTS = [
     "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd", "moe_dispatch_bwd", "moe_gate_bwd",
     "moe_plan", "moe_gate_bwd_params", "moe_input_grad", "moe_expert_ffn_bwd_acc", "moe_trans", "moe_recv_layout",
     "moe_dispatch_after_counts", "moe_set_act_saved", "moe_expert_counts_static", "moe_agg", "moe_calib_copy", "moe_calib_mfma",
+    "moe_calib_round_bf16",
 ]
 
 
@@ -89,6 +90,7 @@ def load() -> ctypes.CDLL:
         lib.moe_agg.argtypes = [vp, vp, ip, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(ctypes.c_size_t), vp]
         lib.moe_calib_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.moe_calib_mfma.argtypes = [vp, ctypes.c_size_t, ip, ctypes.POINTER(ip), ctypes.POINTER(ip), vp]
+        lib.moe_calib_round_bf16.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.moe_recv_layout.argtypes = [vp, ctypes.POINTER(_Layout), vp, ctypes.POINTER(_Layout), vp]
         lib.moe_plan.argtypes = [ctypes.POINTER(_Planner), vp, ctypes.POINTER(_PlanOut), vp]
         _lib = lib
@@ -158,6 +160,14 @@ def calib_mfma(out: torch.Tensor, iters: int) -> float:
     if rc != 0:
         raise MoeError(rc, "moe_calib_mfma", lib.moe_status_string(rc).decode())
     return float(blocks.value) * (threads.value // 64) * iters * 8 * 32768.0
+
+
+def calib_round_bf16(x: torch.Tensor, out: torch.Tensor) -> None:
+    """moe_calib_round_bf16: out[i] (int16 bit patterns) = the library's fp32 -> bf16 rounding of x[i]."""
+    lib = load()
+    rc = lib.moe_calib_round_bf16(_ptr(x, torch.float32, 1, "x"), _ptr(out, torch.int16, x.numel(), "out"), x.numel(), _stream())
+    if rc != 0:
+        raise MoeError(rc, "moe_calib_round_bf16", lib.moe_status_string(rc).decode())
 
 
 class Layout:

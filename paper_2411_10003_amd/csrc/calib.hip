@@ -59,6 +59,13 @@ __global__ __launch_bounds__(512) void calib_mfma_kernel(float* __restrict__ out
     out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// out[i] = the library's fp32 -> bf16 rounding of in[i]
+__global__ void calib_round_kernel(const float* __restrict__ in, uint16_t* __restrict__ out, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = f32_to_bf16(in[i]);
+}
+
 }  // namespace
 
 extern "C" int moe_calib_copy(const void* src, void* dst, size_t bytes, void* stream)
@@ -81,5 +88,14 @@ extern "C" int moe_calib_mfma(float* out, size_t out_floats, int iters, int* blo
     *threads = 512;
     if (out_floats < (size_t)cus * 512) return MOE_ERR_SHAPE;      // every thread writes one float
     hipLaunchKernelGGL(calib_mfma_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, out, iters);
+    return moe_hip_status(hipGetLastError());
+}
+
+extern "C" int moe_calib_round_bf16(const float* in, uint16_t* out, size_t n, void* stream)
+{
+    if (!in || !out) return MOE_ERR_NULL;
+    if (n == 0) return MOE_OK;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(calib_round_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, (hipStream_t)stream, in, out, n);
     return moe_hip_status(hipGetLastError());
 }

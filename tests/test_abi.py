@@ -57,6 +57,7 @@ def test_create_validates_shapes(lib):
     assert create(P=9) == -2 and create(self=4) == -2 and create(G=0) == -2 and create(G=9) == -2
     assert create(E=128, G=64) == 0 and create(E=128, G=65) == -2    # bf16: at most 64 hosted groups
     assert create(dtype=0, E=128, G=65) == 0
+    assert create(d=64, h=1 << 22) == -2 and create(d=1 << 22, h=64) == -2   # bf16: a 256-row tile is addressed in 32 bits
     assert create(dtype=7) == -5 and create(act=3) == -2 and create(renorm=2) == -2
     assert create(T=0) == -2
     assert lib.moe_create(None, None) == -1
