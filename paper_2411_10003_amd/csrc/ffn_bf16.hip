@@ -131,6 +131,10 @@ constexpr size_t LDS_BYTES = RING_BYTES > (size_t)NWAVES * EP_WAVE ? RING_BYTES 
 // K-contiguous operand: [256 rows][32 steps], 64 bytes per row, 16-byte pieces XOR-swizzled by the
 // row so that 16 consecutive rows of one piece cover all banks.
 __device__ __forceinline__ uint32_t kcontig_off(int row, int piece) { return row * 64 + ((piece ^ ((row >> 2) & 3)) << 4); }
+// K-contiguous operand, as NN and NT fetch it: whole 128-byte lines.  A buffer holds 128 rows x 64 steps (two
+// slices of 32), 128 bytes per row, its eight 16-byte pieces XOR-swizzled by the row so that 16 consecutive rows of
+// one piece cover all banks.
+__device__ __forceinline__ uint32_t halfpair_off(int row, int piece8) { return row * 128 + ((piece8 ^ ((row >> 1) & 7)) << 4); }
 // K-major operand: [32 steps][COLS columns]; 64-byte granules of a row XOR-swizzled by the step so
 // that the four steps a transposing load touches fall into different banks.
 template <int COLS>
@@ -305,8 +309,10 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     const int n0 = ct * (DUAL ? BN / 2 : BN);             // first output column (hidden unit for dual)
     const int k_per_seg = (KIND == KIND_TN) ? k_tiles : p.Kseg / BK;
     // slices of this item: all of them, or one part of a split tile; none in the finishing launch
-    const int k_lo = (int)((long)part * k_tiles / parts);
-    const int k_cnt = FIN ? 0 : (int)((long)(part + 1) * k_tiles / parts) - k_lo;
+    // (a K-contiguous operand is fetched two slices at a time: parts begin at even slices)
+    const int k_lo = (int)((long)part * k_tiles / parts) & ~1;
+    const int k_hi = (part + 1 == parts) ? k_tiles : ((int)((long)(part + 1) * k_tiles / parts) & ~1);
+    const int k_cnt = FIN ? 0 : k_hi - k_lo;
 
     // ---- buffer resources: everything outside the valid rows of an operand reads as zero --------
     // Each wave moves two 1-KB pieces of the A slice and two of the B slice per contraction slice.
@@ -353,12 +359,14 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
                 const int krow = L >> 5, pp = L & 31, col = (((pp >> 2) ^ (krow & 3)) << 5) + (pp & 3) * 8;
                 voffA[i] = (uint32_t)((krow * p.lda + col) * 2);
             } else {
-                const int row = L >> 2, piece = (L & 3) ^ ((row >> 2) & 3);
+                // a 1-KB piece is 8 rows x 128 bytes of a 128-row half: lane l reads piece l%8 of row l/8, where the
+                // swizzle of the buffer puts it
+                const int row = blk * 8 + (lane >> 3), piece = (lane & 7) ^ ((row >> 1) & 7);
                 voffA[i] = (uint32_t)((row * p.lda + piece * 8) * 2);
             }
             if (!B_KMAJOR) {
                 ldsB[i] = blk * 1024;
-                const int row = L >> 2, piece = (L & 3) ^ ((row >> 2) & 3);
+                const int row = blk * 8 + (lane >> 3), piece = (lane & 7) ^ ((row >> 1) & 7);
                 voffB[i] = (uint32_t)((row * p.ldb + piece * 8) * 2);
             } else if (DUAL) {
                 // two sub-buffers of [32][128] (8 pieces each); this wave's pieces alternate between them
@@ -411,6 +419,32 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         if (KIND != KIND_TN) return k_per_seg - iss_in_seg;
         const uint32_t hi = soffA > soffB ? soffA : soffB, st = stepA > stepB ? stepA : stepB;
         return (int)((0x3fffffffu - hi) / st) + 1;
+    };
+
+    // NN and NT fetch their K-contiguous operands in whole 128-byte lines: a request group carries, for such an
+    // operand, 128 rows x 64 steps (two slices) instead of 256 rows x 32 steps: group n holds the upper (n even) or
+    // lower (n odd) 128 rows of the tile for slices 2 (n / 2) and 2 (n / 2) + 1.  Same bytes and same number of
+    // instructions per group as a slice, half as many requests to L2.  A K-major operand (the weights of NN) keeps
+    // one slice per group.  PAR: the parity of the group, known where the loop is written out.
+    constexpr bool A_PAIR = !A_KMAJOR, B_PAIR = !B_KMAJOR;
+    const uint32_t halfA = (uint32_t)(128 * p.lda * 2), halfB = (uint32_t)(128 * p.ldb * 2);   // to the lower 128 rows
+    auto issue_group = [&](auto PAR, const rsrc_t ra, const rsrc_t rb0, const rsrc_t rb1) {
+        constexpr int par = decltype(PAR)::value;
+        const uint32_t st = lds0 + (uint32_t)iss_stage * STAGE_BYTES;
+        iss_stage = (iss_stage + 1 == STAGES) ? 0 : iss_stage + 1;
+        const uint32_t oa = (A_PAIR && par) ? soffA + halfA : soffA;
+        const uint32_t ob = (B_PAIR && par) ? soffB + halfB : soffB;
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) dma16(ra, st + ldsA[i], voffA[i], oa);
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) dma16((DUAL && (i & 1)) ? rb1 : rb0, st + OPER_BYTES + ldsB[i], voffB[i], ob);
+        ++iss_in_seg;
+        if (!A_PAIR || par) soffA += A_PAIR ? 2 * stepA : stepA;
+        if (!B_PAIR || par) soffB += B_PAIR ? 2 * stepB : stepB;
+    };
+    // after an odd group (segments hold an even number of slices): the next contraction segment
+    auto group_fixups = [&]() {
+        if (iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
     };
 
     // ---- per-lane fragment addresses inside a stage (step half 0; half 1 is a fixed distance away)
@@ -469,6 +503,34 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             lds_frag_kcontig_at<2048>(fb[1], bb);
         }
     };
+    // Operands fetched in 128-byte lines: fragment 0 of this wave in a 128-row buffer, at the four quarters (16
+    // steps each) of the buffer's two slices; the wave's other fragments lie 32 rows = 4 KB further on.  The upper
+    // row of waves (A) and the waves of the two left columns (B) read the buffer of an even group, the others that
+    // of the odd group after it.
+    uint32_t fpa[4], fpb[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        fpa[v] = halfpair_off(lane & 31, lane >> 5) ^ (uint32_t)(v << 5);
+        fpb[v] = OPER_BYTES + (halfpair_off((wn & 1) * 64 + (lane & 31), lane >> 5) ^ (uint32_t)(v << 5));
+    }
+    auto load_group_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], uint32_t stA, uint32_t stB, auto Q) {
+        constexpr int quarter = decltype(Q)::value;        // 2 * (slice of the pair) + (16-step half of the slice)
+        {
+            const uint32_t a = stA + fpa[quarter];
+            lds_frag_kcontig_at<0>(fa[0], a);
+            lds_frag_kcontig_at<4096>(fa[1], a);
+            lds_frag_kcontig_at<8192>(fa[2], a);
+            lds_frag_kcontig_at<12288>(fa[3], a);
+        }
+        if constexpr (B_KMAJOR) {                          // stB: the buffer of the slice
+#pragma unroll
+            for (int j = 0; j < TN; ++j) lds_frag_kmajor_at<4 * BCOLS * 2, (quarter & 1) * (int)B_HALF>(fb[j], stB + fb_addr[j]);
+        } else {
+            const uint32_t bb = stB + fpb[quarter];
+            lds_frag_kcontig_at<0>(fb[0], bb);
+            lds_frag_kcontig_at<4096>(fb[1], bb);
+        }
+    };
     auto wait_frags = [&]() {
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -503,6 +565,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     // request placed between MFMAs stalls the matrix pipe for several MFMA slots instead).
     static_assert(WGN == 4 && PIECES == 2, "the loop is written for 8 waves");
     if (!FIN && k_cnt > 0) {
+      if constexpr (KIND == KIND_TN) {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         constexpr int L = STAGES - 1;                      // slices requested ahead
         constexpr int SLICE_OPS = 2 * PIECES;              // DMA instructions of one wave per slice
@@ -555,6 +618,80 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         WAIT_VMCNT(0);                                     // the zero-length requests too: the epilogue reuses the ring
         if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
         BLOCK_BARRIER();                                   // and everybody's requests have landed
+          } else {
+        bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+        // NN and NT.  One request group per slice, three ahead: before slice t come the groups 0 .. t + 2, slice t adds
+        // group t + 3 into ring slot (t + 3) % 5, which held group t - 2, last read in slice t - 1.  Slice 2p and 2p + 1
+        // read the K-contiguous operands from the buffers of the groups 2p (upper 128 rows) and 2p + 1 (lower 128
+        // rows), a K-major operand from the buffer of the slice's own group.  What a slice waits for before its
+        // barrier is the data of the next slice: after an even slice the K-major operand's group t + 1 (two groups
+        // may still be on their way), after an odd slice the groups t + 1 and t + 2 of the next pair (one group may).
+        // Contractions have an even number of slices (d and h are multiples of 64; split parts begin at even slices),
+        // so the loop is written out for pairs: slice 0, then pairs of an odd and an even slice, whose two groups are
+        // the two halves of one later pair of slices and need no fixup between them, then the last slice.
+        constexpr int L = 3;
+        constexpr int SLICE_OPS = 2 * PIECES;              // DMA instructions of one wave per group
+        const rsrc_t rnull = make_rsrc(p.A[0], 0);
+        auto real_a = [&]() { return iss_seg ? rA[1] : rA[0]; };
+        auto real_b0 = [&]() { return (KIND == KIND_NT && iss_seg) ? rB[1] : rB[0]; };
+        // groups 0, 1, 2: a contraction has at least two slices
+        issue_group(std::integral_constant<int, 0>{}, real_a(), real_b0(), rB[1]);
+        issue_group(std::integral_constant<int, 1>{}, real_a(), real_b0(), rB[1]);
+        group_fixups();
+        if (k_cnt > 2) issue_group(std::integral_constant<int, 0>{}, real_a(), real_b0(), rB[1]);
+        else issue_group(std::integral_constant<int, 0>{}, rnull, rnull, rnull);
+        WAIT_VMCNT(SLICE_OPS);                             // groups 0 and 1 have landed: slices 0 and 1
+        BLOCK_BARRIER();
+        if (wm == 1) BLOCK_BARRIER();
+        int cur = 0;                                       // ring slot of the slice's own group
+        int pair0 = 0;                                     // ring slot of the even group of the slice's pair
+        const int hA = wm, hB = wn >> 1;                   // which group of a pair holds this wave's rows of A and B
+        auto slot_base = [&](int slot) { return lds0 + (uint32_t)(slot >= STAGES ? slot - STAGES : slot) * STAGE_BYTES; };
+        // One slice of parity PAR; ra .. rb1: the resources of the group it requests (of the opposite parity).
+        auto slice = [&](auto PAR, const rsrc_t ra, const rsrc_t rb0, const rsrc_t rb1) {
+            constexpr int par = decltype(PAR)::value;
+            const uint32_t stA = slot_base(pair0 + hA);
+            const uint32_t stB = B_KMAJOR ? slot_base(cur) : slot_base(pair0 + hB);
+            load_group_frags(fa0, fb0, stA, stB, std::integral_constant<int, 2 * par>{});
+            load_group_frags(fa1, fb1, stA, stB, std::integral_constant<int, 2 * par + 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            issue_group(std::integral_constant<int, 1 - par>{}, ra, rb0, rb1);
+            WAIT_VMCNT(par ? SLICE_OPS : 2 * SLICE_OPS);
+            wait_frags();
+            BLOCK_BARRIER();
+            __builtin_amdgcn_s_setprio(1);
+            mma(fa0, fb0);
+            mma(fa1, fb1);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            BLOCK_BARRIER();
+            cur = (cur + 1 == STAGES) ? 0 : cur + 1;
+            if (par) pair0 = (pair0 + 2 >= STAGES) ? pair0 + 2 - STAGES : pair0 + 2;
+        };
+        // slice 0 requests group 3, the lower rows of slices 2 and 3
+        if (k_cnt > 2) { slice(std::integral_constant<int, 0>{}, real_a(), real_b0(), rB[1]); group_fixups(); }
+        else slice(std::integral_constant<int, 0>{}, rnull, rnull, rnull);
+        asm volatile(".p2align 8\n\t.rept " LOOP_OFF_STR "\n\ts_nop 0\n\t.endr" ::: "memory");
+        // slices 2i + 1 and 2i + 2 request the groups 2i + 4 and 2i + 5: slices 2i + 4 and 2i + 5, if there are any
+        int t = 1;
+        while (t < k_cnt - 1) {
+            const bool more = t + L < k_cnt;               // the pair of slices t + 3, t + 4 exists
+            const int n = more ? min((k_cnt - L - t + 1) / 2, (k_per_seg - iss_in_seg) / 2) : (k_cnt - 1 - t) / 2;
+            const rsrc_t ra = more ? real_a() : rnull;
+            const rsrc_t rb0 = more ? real_b0() : rnull;
+            const rsrc_t rb1 = more ? rB[1] : rnull;
+            for (int i = 0; i < n; ++i) {
+                slice(std::integral_constant<int, 1>{}, ra, rb0, rb1);
+                slice(std::integral_constant<int, 0>{}, ra, rb0, rb1);
+            }
+            t += 2 * n;
+            if (more) group_fixups();
+        }
+        slice(std::integral_constant<int, 1>{}, rnull, rnull, rnull);      // the last slice
+        WAIT_VMCNT(0);                                     // the zero-length requests too: the epilogue reuses the ring
+        if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
+        BLOCK_BARRIER();                                   // and everybody's requests have landed
+      }
     }
 
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");     // the last MFMAs have written back before the accumulators are read
