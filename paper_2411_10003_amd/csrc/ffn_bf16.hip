@@ -35,6 +35,10 @@
 #define LOOP_OFF_STR2(x) #x
 #define LOOP_OFF_STR1(x) LOOP_OFF_STR2(x)
 #define LOOP_OFF_STR LOOP_OFF_STR1(LOOP_OFF)
+#ifndef LOOP_OFF_P
+#define LOOP_OFF_P 4
+#endif
+#define LOOP_OFF_P_STR LOOP_OFF_STR1(LOOP_OFF_P)
 
 namespace {
 
@@ -671,7 +675,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         // slice 0 requests group 3, the lower rows of slices 2 and 3
         if (k_cnt > 2) { slice(std::integral_constant<int, 0>{}, real_a(), real_b0(), rB[1]); group_fixups(); }
         else slice(std::integral_constant<int, 0>{}, rnull, rnull, rnull);
-        asm volatile(".p2align 8\n\t.rept " LOOP_OFF_STR "\n\ts_nop 0\n\t.endr" ::: "memory");
+        asm volatile(".p2align 8\n\t.rept " LOOP_OFF_P_STR "\n\ts_nop 0\n\t.endr" ::: "memory");
         // slices 2i + 1 and 2i + 2 request the groups 2i + 4 and 2i + 5: slices 2i + 4 and 2i + 5, if there are any
         int t = 1;
         while (t < k_cnt - 1) {
