@@ -18,7 +18,11 @@
 // with the accumulators in AGPRs.  An operand whose contraction index is contiguous in memory is
 // kept row-major in LDS and read with 16-byte loads; one whose contraction index is the slow one
 // is kept as it is and read with the transposing LDS load, so no operand is ever transposed in
-// HBM.  Both layouts are XOR-swizzled so that fragment reads are free of bank conflicts.  The MFMA
+// HBM.  Both layouts are XOR-swizzled so that fragment reads are free of bank conflicts.  Every
+// request to L2 is a whole 128-byte line: a K-contiguous operand is therefore fetched two slices
+// at a time for half of the tile's rows (128 rows x 64 steps per ring buffer), a K-major one a
+// slice at a time (32 steps x 256 columns); the L2 channels, not HBM, are what the loop queues at
+// when the same bytes are asked for in 64-byte pieces.  The MFMA
 // is issued with the operands swapped, which leaves every lane with four consecutive output
 // columns of one row.  The two rows of waves of a block alternate between fetching fragments and
 // multiplying, half an iteration apart.
@@ -103,7 +107,7 @@ __device__ __forceinline__ float gelu_grad_f(float z) { const gelu_parts g = gel
 __device__ __forceinline__ float sigmoid_f(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 
 // Tile geometry: 256 x 256 outputs per block, 8 waves of 128 x 64, contraction slices of 32
-// staged through a 5-deep ring of LDS buffers (16 KB per operand per slice): all 160 KB of LDS.
+// staged through a 5-deep ring of LDS buffers (16 KB per operand and buffer): all 160 KB of LDS.
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
 // Row tiles per band of the tile walk, per contraction (measured at d = 4096, h = 14336, SwiGLU; see launch()).
 #ifndef BAND_FWD1
@@ -560,7 +564,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
     };
 
     // ---- main loop, two phases per slice.  In its fetch phase a wave reads the fragments of slice t
-    // from LDS and requests its share of slice t+4; one barrier later, in its multiply phase, it issues
+    // from LDS and requests its share of what lies three or four slices ahead; one barrier later, in its multiply phase, it issues
     // the 16 MFMAs of the slice back to back.  The upper row of waves runs one barrier interval behind
     // the lower one; waves w and w+4 share a SIMD, so while one of them feeds the matrix pipe the other
     // collects its operands.  With LDS reads and MFMAs alone this loop runs at the MFMA rate; what it
