@@ -173,6 +173,23 @@ def test_full_config(G, orc, ci):
     _check_pass(G, orc, case, hd, b, label=f"cfg{ci}")
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("T,h,parts", [(10240, 6272, 3), (8192, 8256, 4)])
+def test_last_round_split_in_three_and_four_parts(G, orc, T, h, parts):
+    """Shapes whose last round of fwd2 and bwd2 is cut along the contraction into three and four parts, with part
+    boundaries that would fall on odd slices (196 and 258 slices) if the kernel did not move them to even ones."""
+    cfg = wl.scaled(wl.CONFIGS[2], T=T, d=256, h=h)
+    case = G.Case(cfg)
+    row_tiles = G.ffn_row_tiles([case.group_rows(g) for g in range(case.G)])
+    n_blocks = torch.cuda.get_device_properties(0).multi_processor_count // 8 * 8
+    k_slices = h // 32
+    assert min(4, n_blocks // len(row_tiles), k_slices // 64) == parts
+    assert any((i * k_slices // parts) % 2 == 1 for i in range(1, parts))
+    hd = G.make_handle(cfg)
+    b = G.binding.LayerBuffers(hd, cfg.backward)
+    _check_pass(G, orc, case, hd, b, label=f"split{parts}")
+
+
 @pytest.mark.timeout(900)
 def test_drift_sweep(G, orc):
     """Ten iterations of the skew/drift workload: alpha cycles through {0, 0.8, 1.5}, the rank
