@@ -136,10 +136,7 @@ constexpr size_t RING_BYTES = (size_t)STAGES * STAGE_BYTES;
 constexpr size_t LDS_BYTES = RING_BYTES > (size_t)NWAVES * EP_WAVE ? RING_BYTES : (size_t)NWAVES * EP_WAVE;
 
 // ---- LDS layouts (byte offsets inside one operand buffer) --------------------------------------
-// K-contiguous operand: [256 rows][32 steps], 64 bytes per row, 16-byte pieces XOR-swizzled by the
-// row so that 16 consecutive rows of one piece cover all banks.
-__device__ __forceinline__ uint32_t kcontig_off(int row, int piece) { return row * 64 + ((piece ^ ((row >> 2) & 3)) << 4); }
-// K-contiguous operand, as NN and NT fetch it: whole 128-byte lines.  A buffer holds 128 rows x 64 steps (two
+// K-contiguous operand (NN and NT fetch it in whole 128-byte lines): a buffer holds 128 rows x 64 steps (two
 // slices of 32), 128 bytes per row, its eight 16-byte pieces XOR-swizzled by the row so that 16 consecutive rows of
 // one piece cover all banks.
 __device__ __forceinline__ uint32_t halfpair_off(int row, int piece8) { return row * 128 + ((piece8 ^ ((row >> 1) & 7)) << 4); }
@@ -455,61 +452,38 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         if (iss_in_seg == k_per_seg) { iss_in_seg = 0; ++iss_seg; soffA = 0; soffB = 0; }
     };
 
-    // ---- per-lane fragment addresses inside a stage (step half 0; half 1 is a fixed distance away)
+    // ---- per-lane fragment addresses inside a ring buffer.  The buffer's base is the only part of a fragment
+    // address that changes from slice to slice, and every vector instruction of the fetching wave takes an issue
+    // slot from the matrix instructions of its partner: fragments that lie a constant distance apart share one
+    // address register and differ in the instruction's immediate offset.
+    static_assert(TM == 4 && TN == 2, "the fragment reads below are written out for 4 x 2 fragments");
+    // K-major operands (step half 0; half 1 is 16 steps further down)
     uint32_t fa_addr[TM], fb_addr[TN];
-    constexpr uint32_t A_HALF = A_KMAJOR ? 16 * (BM * 2) : 0;      // K-major: 16 steps further down
+    constexpr uint32_t A_HALF = 16 * (BM * 2);
     constexpr int BCOLS = DUAL ? BN / 2 : BN;
-    constexpr uint32_t B_HALF = B_KMAJOR ? 16 * (BCOLS * 2) : 0;
+    constexpr uint32_t B_HALF = 16 * (BCOLS * 2);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int r = wm * WM + i * 32;
-        if (A_KMAJOR) {
-            const int b = lane >> 4, s = lane & 15;
-            fa_addr[i] = kmajor_off<BM>(8 * (b >> 1) + (s >> 2), r + 16 * (b & 1) + 4 * (s & 3));
-        } else {
-            fa_addr[i] = kcontig_off(r + (lane & 31), lane >> 5);
-        }
+        const int b = lane >> 4, s = lane & 15;
+        fa_addr[i] = kmajor_off<BM>(8 * (b >> 1) + (s >> 2), wm * WM + i * 32 + 16 * (b & 1) + 4 * (s & 3));
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        if (!B_KMAJOR) {
-            fb_addr[j] = OPER_BYTES + kcontig_off(wn * WN + j * 32 + (lane & 31), lane >> 5);
-        } else {
-            const int b = lane >> 4, s = lane & 15;
-            const int krow = 8 * (b >> 1) + (s >> 2), cofs = 16 * (b & 1) + 4 * (s & 3);
-            if (DUAL)   // even fragments from the W1 sub-buffer, odd ones from the W3 sub-buffer
-                fb_addr[j] = OPER_BYTES + (j & 1) * 8192 + kmajor_off<BN / 2>(krow, wn * (WN / 2) + (j >> 1) * 32 + cofs);
-            else
-                fb_addr[j] = OPER_BYTES + kmajor_off<BN>(krow, wn * WN + j * 32 + cofs);
-        }
+        const int b = lane >> 4, s = lane & 15;
+        const int krow = 8 * (b >> 1) + (s >> 2), cofs = 16 * (b & 1) + 4 * (s & 3);
+        if (DUAL)   // even fragments from the W1 sub-buffer, odd ones from the W3 sub-buffer
+            fb_addr[j] = OPER_BYTES + (j & 1) * 8192 + kmajor_off<BN / 2>(krow, wn * (WN / 2) + (j >> 1) * 32 + cofs);
+        else
+            fb_addr[j] = OPER_BYTES + kmajor_off<BN>(krow, wn * WN + j * 32 + cofs);
     }
-    // The stage base is the only part of a fragment address that changes from slice to slice, and every vector
-    // instruction of the fetching wave takes an issue slot from the matrix instructions of its partner: fragments
-    // that lie a constant distance apart (K-contiguous: 32 rows = 2 KB; the second 16 steps of a K-major operand)
-    // share one address register and differ in the instruction's immediate offset.
-    static_assert(TM == 4 && TN == 2, "the fragment reads below are written out for 4 x 2 fragments");
-    uint32_t fa_h1 = fa_addr[0] ^ 32u, fb_h1 = fb_addr[0] ^ 32u;       // K-contiguous: step half 1 of fragment 0
+    // TN: both operands K-major, a slice per ring buffer
     auto load_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int stage, auto HALF) {
         constexpr int half = decltype(HALF)::value;
         const uint32_t st = lds0 + (uint32_t)stage * STAGE_BYTES;
-        if constexpr (A_KMAJOR) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) lds_frag_kmajor_at<4 * BM * 2, half * (int)A_HALF>(fa[i], st + fa_addr[i]);
-        } else {
-            const uint32_t a = st + (half ? fa_h1 : fa_addr[0]);
-            lds_frag_kcontig_at<0>(fa[0], a);
-            lds_frag_kcontig_at<2048>(fa[1], a);
-            lds_frag_kcontig_at<4096>(fa[2], a);
-            lds_frag_kcontig_at<6144>(fa[3], a);
-        }
-        if constexpr (B_KMAJOR) {
+        for (int i = 0; i < TM; ++i) lds_frag_kmajor_at<4 * BM * 2, half * (int)A_HALF>(fa[i], st + fa_addr[i]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) lds_frag_kmajor_at<4 * BCOLS * 2, half * (int)B_HALF>(fb[j], st + fb_addr[j]);
-        } else {
-            const uint32_t bb = st + (half ? fb_h1 : fb_addr[0]);
-            lds_frag_kcontig_at<0>(fb[0], bb);
-            lds_frag_kcontig_at<2048>(fb[1], bb);
-        }
+        for (int j = 0; j < TN; ++j) lds_frag_kmajor_at<4 * BCOLS * 2, half * (int)B_HALF>(fb[j], st + fb_addr[j]);
     };
     // Operands fetched in 128-byte lines: fragment 0 of this wave in a 128-row buffer, at the four quarters (16
     // steps each) of the buffer's two slices; the wave's other fragments lie 32 rows = 4 KB further on.  The upper
