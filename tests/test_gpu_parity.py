@@ -229,6 +229,10 @@ FFN_CASES = [
     # parts, over both segments of the SwiGLU input gradient) and are finished by the second launch
     _cfg(3, T=500, d=128, h=4096, backward=True),
     _cfg(1, T=600, d=4096, h=128, backward=True),
+    # the shortest contractions there are: two slices (one pair) per segment, so the loop's first and last slice are
+    # all of it, and the SwiGLU input gradient changes segment after its first pair
+    _cfg(3, T=700, d=64, h=64, backward=True),
+    _cfg(1, T=700, d=64, h=192, backward=True),
 ]
 
 
