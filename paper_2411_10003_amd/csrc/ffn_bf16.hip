@@ -519,13 +519,17 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         __builtin_amdgcn_sched_barrier(0);                 // no MFMA moves above the wait
     };
 
+    // NN and NT start their accumulators with the first products of slice 0 (a matrix instruction that takes zero
+    // as its addend) instead of clearing 128 registers per tile; TN, whose groups may be empty, clears them.
     f32x16 acc[TM][TN];
+    if (KIND == KIND_TN || FIN) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    }
 
     // the TM*TN products of one 16-step.  The accumulators are pinned to AGPRs, which leaves the
     // VGPRs of the wave to fragments and addresses.
@@ -630,7 +634,14 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         const int hA = wm, hB = wn >> 1;                   // which group of a pair holds this wave's rows of A and B
         auto slot_base = [&](int slot) { return lds0 + (uint32_t)(slot >= STAGES ? slot - STAGES : slot) * STAGE_BYTES; };
         // One slice of parity PAR; ra .. rb1: the resources of the group it requests (of the opposite parity).
-        auto slice = [&](auto PAR, const rsrc_t ra, const rsrc_t rb0, const rsrc_t rb1) {
+        auto mma_first = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {      // acc = products (+ 0)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(acc[i][j]) : "v"(fb[j]), "v"(fa[i]));
+        };
+        auto slice = [&](auto PAR, auto FIRST, const rsrc_t ra, const rsrc_t rb0, const rsrc_t rb1) {
             constexpr int par = decltype(PAR)::value;
             const uint32_t stA = slot_base(pair0 + hA);
             const uint32_t stB = B_KMAJOR ? slot_base(cur) : slot_base(pair0 + hB);
@@ -642,7 +653,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             wait_frags();
             BLOCK_BARRIER();
             __builtin_amdgcn_s_setprio(1);
-            mma(fa0, fb0);
+            if constexpr (decltype(FIRST)::value) mma_first(fa0, fb0); else mma(fa0, fb0);
             mma(fa1, fb1);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
@@ -651,8 +662,8 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             if (par) pair0 = (pair0 + 2 >= STAGES) ? pair0 + 2 - STAGES : pair0 + 2;
         };
         // slice 0 requests group 3, the lower rows of slices 2 and 3
-        if (k_cnt > 2) { slice(std::integral_constant<int, 0>{}, real_a(), real_b0(), rB[1]); group_fixups(); }
-        else slice(std::integral_constant<int, 0>{}, rnull, rnull, rnull);
+        if (k_cnt > 2) { slice(std::integral_constant<int, 0>{}, std::true_type{}, real_a(), real_b0(), rB[1]); group_fixups(); }
+        else slice(std::integral_constant<int, 0>{}, std::true_type{}, rnull, rnull, rnull);
         asm volatile(".p2align 8\n\t.rept " LOOP_OFF_P_STR "\n\ts_nop 0\n\t.endr" ::: "memory");
         // slices 2i + 1 and 2i + 2 request the groups 2i + 4 and 2i + 5: slices 2i + 4 and 2i + 5, if there are any
         int t = 1;
@@ -663,13 +674,13 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
             const rsrc_t rb0 = more ? real_b0() : rnull;
             const rsrc_t rb1 = more ? rB[1] : rnull;
             for (int i = 0; i < n; ++i) {
-                slice(std::integral_constant<int, 1>{}, ra, rb0, rb1);
-                slice(std::integral_constant<int, 0>{}, ra, rb0, rb1);
+                slice(std::integral_constant<int, 1>{}, std::false_type{}, ra, rb0, rb1);
+                slice(std::integral_constant<int, 0>{}, std::false_type{}, ra, rb0, rb1);
             }
             t += 2 * n;
             if (more) group_fixups();
         }
-        slice(std::integral_constant<int, 1>{}, rnull, rnull, rnull);      // the last slice
+        slice(std::integral_constant<int, 1>{}, std::false_type{}, rnull, rnull, rnull);      // the last slice
         WAIT_VMCNT(0);                                     // the zero-length requests too: the epilogue reuses the ring
         if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
         BLOCK_BARRIER();                                   // and everybody's requests have landed
