@@ -604,7 +604,7 @@ __global__ __launch_bounds__(NT) void grouped_gemm_kernel(const GemmParams p)
         WAIT_VMCNT(0);                                     // the zero-length requests too: the epilogue reuses the ring
         if (wm == 0) BLOCK_BARRIER();                      // both rows have passed the same number of barriers
         BLOCK_BARRIER();                                   // and everybody's requests have landed
-          } else {
+      } else {
         bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
         // NN and NT.  One request group per slice, three ahead: before slice t come the groups 0 .. t + 2, slice t adds
         // group t + 3 into ring slot (t + 3) % 5, which held group t - 2, last read in slice t - 1.  Slice 2p and 2p + 1
